@@ -1,0 +1,174 @@
+/*
+ * kvtc.h -- C ABI of the MI355X (gfx950) KV-cache transform coder.
+ *
+ * The library implements the data-parallel hot path of "KV Cache Transform
+ * Coding for Compact Storage in LLM Inference" (KVTC):
+ *
+ *   encode (paper, Section "Method", mode "Compression"; Sections "Feature
+ *           decorrelation", eq. 3, and "Quantization"):
+ *       d = (x - mu) V_kept            per token, bf16 matrix-core product, fp32 sums
+ *       per token and per group of subsequent PCA coordinates: min-max uniform
+ *       quantisation at the group's calibrated width with a shared fp16 shift
+ *       and fp16 scale; coordinates with zero width are never computed;
+ *       codes are bit-packed into one fixed-size record per token.
+ *   decode (same Section, mode "Decompression"; eq. 3 right-hand side):
+ *       unpack, d_hat = shift + code * scale, x_hat = d_hat V_kept^T + mu.
+ *
+ * Calibration (PCA basis, mean, bit allocation) is done elsewhere and enters
+ * as data through kvtc_plan_create.  The entropy stage (DEFLATE, Section
+ * "Entropy coding") is not part of this library.
+ *
+ * Record format (the paper only says "packed into a single byte array"):
+ * a record is a little-endian bit string of R = 4*ceil((32 G + sum n_g b_g)/32)
+ * bytes: G header dwords (group g: fp16 shift in bits 0-15, fp16 scale in
+ * bits 16-31), then every kept coordinate's code in PCA order, width b_g,
+ * least significant bit first, no gaps; zero padding to 32 bits.  A tensor's
+ * stream is its records back to back in token order.
+ *
+ * Numerics of the code decision (both sides of any comparison must use them):
+ *   lo/hi = min/max of the group's fp32 coefficients; shift = largest fp16 <= lo;
+ *   scale = smallest fp16 >= (hi - shift)/(2^b - 1) (fp32 subtract and divide);
+ *   code = clamp(round_half_even((d - shift) * (1/scale)), 0, 2^b - 1), each
+ *   operation one fp32 operation; scale == 0 gives code 0; shift and scale
+ *   saturate at +-65504.  NaN inputs give unspecified codes and never fault.
+ *
+ * All pointers named *_dev are device pointers, all named *_host host
+ * pointers.  `stream` arguments are a hipStream_t passed as void*.
+ * Every function returns a kvtc_status; kvtc_last_error() gives a
+ * thread-local message for the last non-OK status.  No function throws.
+ * encode/decode calls never allocate and never synchronise; they are ordered
+ * on the given stream.
+ */
+#ifndef KVTC_H
+#define KVTC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kvtc_plan kvtc_plan;     /* one per (layer, K or V, compression ratio); immutable */
+typedef struct kvtc_batch kvtc_batch;   /* a set of plans addressable from one batched launch   */
+typedef void* kvtc_stream;              /* a hipStream_t */
+
+typedef enum {
+    KVTC_OK = 0,
+    KVTC_E_ARG = 1,          /* null pointer, negative size, bad alignment, inconsistent plan   */
+    KVTC_E_UNSUPPORTED = 2,  /* valid request the kernels cannot serve (see kvtc_plan_create)   */
+    KVTC_E_SMALL = 3,        /* output capacity / input size below n_tokens * record bytes      */
+    KVTC_E_HIP = 4,          /* a HIP runtime call failed                                        */
+    KVTC_E_NOMEM = 5         /* host or device allocation failed (plan/batch creation only)     */
+} kvtc_status;
+
+typedef enum { KVTC_BF16 = 0, KVTC_F32 = 1 } kvtc_dtype;
+
+/* A kept group: n subsequent kept PCA coordinates sharing one shift/scale, each coded on `bits` bits. */
+typedef struct { uint16_t n; uint8_t bits; uint8_t reserved; } kvtc_group;
+
+/* One tensor of a batched call.  x_row0 is the row of the job's first token in the shared
+ * feature array; the job's stream starts at offsets[job] in the shared stream buffer. */
+typedef struct { int32_t plan; int32_t n_tokens; int64_t x_row0; } kvtc_job;
+
+/*
+ * Build a plan (paper, Section "Method", mode "Calibration", gives the inputs:
+ * mean mu, basis V trimmed to the coordinates with non-zero width, and the
+ * per-group widths and sizes).
+ *   p            features per token; multiple of 64
+ *   r            kept coordinates, 16 <= r <= 1024, r <= 1024
+ *   mu_host      [p] fp32
+ *   v_kept_host  [p][r] row-major bf16 bit patterns (column j = j-th kept coordinate)
+ *   groups_host  n_groups kept groups in PCA order; sum of n must equal r
+ * The arrays are copied; they may be freed when the call returns.  The call
+ * allocates device memory on the current device and synchronises `stream`.
+ * Errors: KVTC_E_ARG for null/inconsistent input or bits outside 1..16;
+ * KVTC_E_UNSUPPORTED if a group size is not a multiple of 16 (the kernels work
+ * on 16-coordinate blocks; the group sizes 16, 64, 256, 1024 all qualify) or the
+ * record is too large for the kernels' on-chip staging.
+ */
+kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host,
+                             const uint16_t* v_kept_host, int n_groups,
+                             const kvtc_group* groups_host, kvtc_stream stream);
+void kvtc_plan_destroy(kvtc_plan* plan);                                  /* NULL is a no-op */
+size_t kvtc_record_bytes(const kvtc_plan* plan);                          /* R; 0 for NULL    */
+size_t kvtc_encoded_bytes(const kvtc_plan* plan, int64_t n_tokens);       /* n_tokens * R     */
+
+/*
+ * Encode one tensor (paper, "Compression": project, quantise, pack).
+ *   x_dev     [n_tokens][ld_x] elements of `dtype`, row-major, ld_x >= p, 16-byte aligned
+ *             base and row pitch.  fp32 inputs are rounded to bf16 (nearest even) on load.
+ *   out_dev   receives n_tokens records; 16-byte aligned; out_cap >= n_tokens * R else
+ *             KVTC_E_SMALL and nothing is written.
+ * n_tokens == 0 is KVTC_OK and does nothing.
+ */
+kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype,
+                        int64_t n_tokens, int64_t ld_x, void* out_dev, size_t out_cap,
+                        kvtc_stream stream);
+
+/*
+ * Decode one tensor (paper, "Decompression": unpack, dequantise, back-project, add mu).
+ *   in_dev    n_tokens records, 16-byte aligned; in_bytes >= n_tokens * R else KVTC_E_SMALL.
+ *   x_out_dev [n_tokens][ld_x] of `dtype`; results are rounded to nearest even for bf16.
+ */
+kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_bytes,
+                        int64_t n_tokens, void* x_out_dev, kvtc_dtype dtype, int64_t ld_x,
+                        kvtc_stream stream);
+
+/*
+ * Batched / ragged calls: many tensors (jobs), each with its own plan and length, in
+ * one launch per direction.  A kvtc_batch makes the plans' descriptors addressable
+ * from the device; it copies what it needs, but the plans must outlive it.
+ * At most 2048 jobs per call (KVTC_E_UNSUPPORTED beyond).
+ */
+kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, int n_plans,
+                              kvtc_stream stream);
+void kvtc_batch_destroy(kvtc_batch* batch);
+
+/*
+ * Stream offsets of a ragged batch, computed on the GPU:
+ *   offsets_dev[j] = sum_{i<j} jobs_dev[i].n_tokens * R(plan of job i),  j = 0..n_jobs
+ * (an exclusive prefix sum; offsets_dev[n_jobs] is the total stream size).
+ * jobs_dev: device array of n_jobs kvtc_job.  Jobs with a plan index outside the
+ * batch or n_tokens < 0 count as empty here and are reported by the encode/decode call.
+ */
+kvtc_status kvtc_offsets(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs,
+                         uint64_t* offsets_dev, kvtc_stream stream);
+
+/*
+ * Encode / decode every job.  x_base_dev is the shared feature array (rows of ld_x
+ * elements); job j reads/writes rows x_row0 .. x_row0 + n_tokens - 1 and the stream
+ * bytes offsets_dev[j] .. offsets_dev[j+1] - 1 of the shared stream buffer.
+ * The host cannot see device-resident sizes without synchronising, so capacity is
+ * checked on the device: a job whose stream would end beyond `cap`, or whose plan
+ * index / token count is invalid, is skipped entirely and *status_dev is set to
+ * 1 + (index of the lowest such job); it stays 0 when every job ran.  The caller
+ * zeroes *status_dev beforehand and reads it after synchronising.
+ */
+kvtc_status kvtc_encode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs,
+                              const void* x_base_dev, kvtc_dtype dtype, int64_t ld_x,
+                              const uint64_t* offsets_dev, void* out_base_dev, size_t out_cap,
+                              uint32_t* status_dev, kvtc_stream stream);
+kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs,
+                              const void* in_base_dev, size_t in_bytes,
+                              const uint64_t* offsets_dev, void* x_out_base_dev,
+                              kvtc_dtype dtype, int64_t ld_x, uint32_t* status_dev,
+                              kvtc_stream stream);
+
+/* Thread-local text for the last non-OK status returned on this thread (static storage). */
+const char* kvtc_last_error(void);
+
+/*
+ * Host-only helpers that expose the kernels' scalar numerics for CPU tests
+ * (no GPU needed): the directed fp32 -> fp16 roundings used for shift (down)
+ * and scale (up), and the code decision for one value.
+ */
+uint16_t kvtc_host_f16_round_down(float x);
+uint16_t kvtc_host_f16_round_up(float x);
+void kvtc_host_group_header(float lo, float hi, int bits, uint16_t* shift16, uint16_t* scale16);
+uint32_t kvtc_host_code(float d, uint16_t shift16, uint16_t scale16, int bits);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVTC_H */

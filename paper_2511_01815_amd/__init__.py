@@ -1,0 +1,13 @@
+"""MI355X-native KV-cache transform coder (encode/decode hot path of KVTC).
+
+Thin ctypes binding over libkvtc.so (HIP kernels for gfx950 behind a C ABI, see
+include/kvtc.h).  PyTorch is only used by callers for device memory and streams.
+Importing the package never needs the GPU; calling into it without a built
+library raises.
+"""
+from .binding import (  # noqa: F401
+    KVTC_BF16, KVTC_F32, KvtcError, Plan, Batch, lib, lib_path,
+    kvtc_plan_create, kvtc_plan_destroy, kvtc_record_bytes, kvtc_encoded_bytes,
+    kvtc_encode, kvtc_decode, kvtc_batch_create, kvtc_batch_destroy, kvtc_offsets,
+    kvtc_encode_batch, kvtc_decode_batch, kvtc_last_error, JOB_DTYPE, make_jobs,
+)

@@ -1,0 +1,214 @@
+"""ctypes marshalling for the C ABI in include/kvtc.h -- no arithmetic happens here."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+KVTC_BF16, KVTC_F32 = 0, 1
+_STATUS = {0: "KVTC_OK", 1: "KVTC_E_ARG", 2: "KVTC_E_UNSUPPORTED", 3: "KVTC_E_SMALL", 4: "KVTC_E_HIP", 5: "KVTC_E_NOMEM"}
+
+# layout of kvtc_job: { int32 plan; int32 n_tokens; int64 x_row0; }
+JOB_DTYPE = np.dtype([("plan", "<i4"), ("n_tokens", "<i4"), ("x_row0", "<i8")])
+
+
+class KvtcError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+class _Group(C.Structure):
+    _fields_ = [("n", C.c_uint16), ("bits", C.c_uint8), ("reserved", C.c_uint8)]
+
+
+def lib_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvtc.so")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(path)
+        vp, i64, sz = C.c_void_p, C.c_int64, C.c_size_t
+        L.kvtc_plan_create.argtypes = [C.POINTER(vp), C.c_int, C.c_int, vp, vp, C.c_int, vp, vp]
+        L.kvtc_plan_create.restype = C.c_int
+        L.kvtc_plan_destroy.argtypes = [vp]
+        L.kvtc_plan_destroy.restype = None
+        L.kvtc_record_bytes.argtypes = [vp]
+        L.kvtc_record_bytes.restype = sz
+        L.kvtc_encoded_bytes.argtypes = [vp, i64]
+        L.kvtc_encoded_bytes.restype = sz
+        L.kvtc_encode.argtypes = [vp, vp, C.c_int, i64, i64, vp, sz, vp]
+        L.kvtc_encode.restype = C.c_int
+        L.kvtc_decode.argtypes = [vp, vp, sz, i64, vp, C.c_int, i64, vp]
+        L.kvtc_decode.restype = C.c_int
+        L.kvtc_batch_create.argtypes = [C.POINTER(vp), C.POINTER(vp), C.c_int, vp]
+        L.kvtc_batch_create.restype = C.c_int
+        L.kvtc_batch_destroy.argtypes = [vp]
+        L.kvtc_batch_destroy.restype = None
+        L.kvtc_offsets.argtypes = [vp, vp, C.c_int, vp, vp]
+        L.kvtc_offsets.restype = C.c_int
+        L.kvtc_encode_batch.argtypes = [vp, vp, C.c_int, vp, C.c_int, i64, vp, vp, sz, vp, vp]
+        L.kvtc_encode_batch.restype = C.c_int
+        L.kvtc_decode_batch.argtypes = [vp, vp, C.c_int, vp, sz, vp, vp, C.c_int, i64, vp, vp]
+        L.kvtc_decode_batch.restype = C.c_int
+        L.kvtc_last_error.argtypes = []
+        L.kvtc_last_error.restype = C.c_char_p
+        L.kvtc_host_f16_round_down.argtypes = [C.c_float]
+        L.kvtc_host_f16_round_down.restype = C.c_uint16
+        L.kvtc_host_f16_round_up.argtypes = [C.c_float]
+        L.kvtc_host_f16_round_up.restype = C.c_uint16
+        L.kvtc_host_group_header.argtypes = [C.c_float, C.c_float, C.c_int, C.POINTER(C.c_uint16), C.POINTER(C.c_uint16)]
+        L.kvtc_host_group_header.restype = None
+        L.kvtc_host_code.argtypes = [C.c_float, C.c_uint16, C.c_uint16, C.c_int]
+        L.kvtc_host_code.restype = C.c_uint32
+        _lib = L
+    return _lib
+
+
+def kvtc_last_error() -> str:
+    return lib().kvtc_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise KvtcError(status, kvtc_last_error())
+
+
+def _ptr(t) -> Optional[int]:
+    """Device/host address of a torch tensor, numpy array, int or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+# ---- plain wrappers, one per C entry point ---------------------------------------------------
+
+def kvtc_plan_create(p: int, r: int, mu_host: np.ndarray, v_kept_host: np.ndarray,
+                     groups: Sequence[Sequence[int]], stream=None) -> int:
+    mu = np.ascontiguousarray(mu_host, dtype=np.float32)
+    v = np.ascontiguousarray(v_kept_host, dtype=np.uint16)
+    assert mu.shape == (p,) and v.shape == (p, r), (mu.shape, v.shape)
+    arr = (_Group * len(groups))(*[_Group(int(n), int(b), 0) for n, b in groups])
+    out = C.c_void_p()
+    _check(lib().kvtc_plan_create(C.byref(out), p, r, mu.ctypes.data, v.ctypes.data, len(groups),
+                                  C.cast(arr, C.c_void_p), _stream(stream)))
+    return out.value
+
+
+def kvtc_plan_destroy(plan: int) -> None:
+    lib().kvtc_plan_destroy(plan)
+
+
+def kvtc_record_bytes(plan: int) -> int:
+    return lib().kvtc_record_bytes(plan)
+
+
+def kvtc_encoded_bytes(plan: int, n_tokens: int) -> int:
+    return lib().kvtc_encoded_bytes(plan, n_tokens)
+
+
+def kvtc_encode(plan: int, x_dev, dtype: int, n_tokens: int, ld_x: int, out_dev, out_cap: int, stream=None) -> None:
+    _check(lib().kvtc_encode(plan, _ptr(x_dev), dtype, n_tokens, ld_x, _ptr(out_dev), out_cap, _stream(stream)))
+
+
+def kvtc_decode(plan: int, in_dev, in_bytes: int, n_tokens: int, x_out_dev, dtype: int, ld_x: int, stream=None) -> None:
+    _check(lib().kvtc_decode(plan, _ptr(in_dev), in_bytes, n_tokens, _ptr(x_out_dev), dtype, ld_x, _stream(stream)))
+
+
+def kvtc_batch_create(plans: Sequence[int], stream=None) -> int:
+    arr = (C.c_void_p * len(plans))(*plans)
+    out = C.c_void_p()
+    _check(lib().kvtc_batch_create(C.byref(out), arr, len(plans), _stream(stream)))
+    return out.value
+
+
+def kvtc_batch_destroy(batch: int) -> None:
+    lib().kvtc_batch_destroy(batch)
+
+
+def kvtc_offsets(batch: int, jobs_dev, n_jobs: int, offsets_dev, stream=None) -> None:
+    _check(lib().kvtc_offsets(batch, _ptr(jobs_dev), n_jobs, _ptr(offsets_dev), _stream(stream)))
+
+
+def kvtc_encode_batch(batch: int, jobs_dev, n_jobs: int, x_base_dev, dtype: int, ld_x: int, offsets_dev,
+                      out_base_dev, out_cap: int, status_dev, stream=None) -> None:
+    _check(lib().kvtc_encode_batch(batch, _ptr(jobs_dev), n_jobs, _ptr(x_base_dev), dtype, ld_x, _ptr(offsets_dev),
+                                   _ptr(out_base_dev), out_cap, _ptr(status_dev), _stream(stream)))
+
+
+def kvtc_decode_batch(batch: int, jobs_dev, n_jobs: int, in_base_dev, in_bytes: int, offsets_dev, x_out_base_dev,
+                      dtype: int, ld_x: int, status_dev, stream=None) -> None:
+    _check(lib().kvtc_decode_batch(batch, _ptr(jobs_dev), n_jobs, _ptr(in_base_dev), in_bytes, _ptr(offsets_dev),
+                                   _ptr(x_out_base_dev), dtype, ld_x, _ptr(status_dev), _stream(stream)))
+
+
+def make_jobs(plan_idx: Sequence[int], n_tokens: Sequence[int], x_row0: Sequence[int]) -> np.ndarray:
+    """Host image of a kvtc_job array (copy it to the device as raw bytes)."""
+    jobs = np.zeros(len(plan_idx), dtype=JOB_DTYPE)
+    jobs["plan"], jobs["n_tokens"], jobs["x_row0"] = plan_idx, n_tokens, x_row0
+    return jobs
+
+
+# ---- small owners so handles are released --------------------------------------------------------
+
+class Plan:
+    """Owns a kvtc_plan handle."""
+
+    def __init__(self, p: int, r: int, mu_host, v_kept_host, groups, stream=None):
+        self.p, self.r, self.groups = p, r, [(int(n), int(b)) for n, b in groups]
+        self.handle = kvtc_plan_create(p, r, mu_host, v_kept_host, self.groups, stream)
+        self.record_bytes = kvtc_record_bytes(self.handle)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            kvtc_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Batch:
+    """Owns a kvtc_batch handle (and keeps its plans alive)."""
+
+    def __init__(self, plans: Sequence[Plan], stream=None):
+        self.plans = list(plans)
+        self.handle = kvtc_batch_create([p.handle for p in self.plans], stream)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            kvtc_batch_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,495 @@
+// Host side of the C ABI declared in include/kvtc.h: argument checks, plan compilation
+// (swizzling the basis into matrix-core operand fragments, block/group tables), launches,
+// and the on-device prefix sum of stream offsets.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kvtc_dev.h"
+#include "kvtc_numeric.h"
+
+namespace kvtc {
+hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int grid, size_t lds_bytes, hipStream_t stream);
+hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int grid, size_t lds_bytes, hipStream_t stream);
+}  // namespace kvtc
+
+using namespace kvtc;
+
+struct kvtc_plan {
+    PlanDev h;              // host copy of the descriptor (device pointers inside)
+    void* blob;             // one device allocation holding everything
+    PlanDev* desc_dev;      // the descriptor inside the blob
+    size_t record_bytes;
+};
+
+struct kvtc_batch {
+    PlanDev* plans_dev;
+    int n_plans;
+    int enc_lds, dec_lds;   // max over the plans
+    std::vector<int32_t> rec_dwords;
+    uint32_t* rec_dwords_dev;
+};
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+kvtc_status fail(kvtc_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+float bf16_bits_to_float(uint16_t b) { return bits_f32((uint32_t)b << 16); }
+
+int cu_count() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// position of coordinate/feature row `rho` of an MFMA tile inside the lane's 16 results:
+// the 32x32 accumulator gives lane half hh, register i the row 8*(i/4) + 4*hh + i%4; mapping
+// row rho to index 16*hh + i makes each lane own 16 consecutive indices.
+int permuted_index(int rho) {
+    const int q = rho >> 3, hh = (rho >> 2) & 1, m = rho & 3;
+    return 16 * hh + 4 * q + m;
+}
+
+bool dtype_ok(kvtc_dtype d) { return d == KVTC_BF16 || d == KVTC_F32; }
+size_t elem_size(kvtc_dtype d) { return d == KVTC_BF16 ? 2 : 4; }
+
+__global__ void __launch_bounds__(256) offsets_kernel(const uint32_t* rec_dwords, int n_plans, const kvtc_job* jobs,
+                                                     int n_jobs, uint64_t* offsets) {
+    __shared__ uint64_t s[256];
+    __shared__ uint64_t carry;
+    const int tid = threadIdx.x;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < n_jobs; base += 256) {
+        const int j = base + tid;
+        uint64_t bytes = 0;
+        if (j < n_jobs) {
+            const kvtc_job jb = jobs[j];
+            if (jb.plan >= 0 && jb.plan < n_plans && jb.n_tokens > 0)
+                bytes = (uint64_t)jb.n_tokens * rec_dwords[jb.plan] * 4ull;
+        }
+        s[tid] = bytes;
+        __syncthreads();
+        for (int d = 1; d < 256; d <<= 1) {
+            const uint64_t v = tid >= d ? s[tid - d] : 0ull;
+            __syncthreads();
+            s[tid] += v;
+            __syncthreads();
+        }
+        const uint64_t c = carry;
+        if (j < n_jobs) offsets[j] = c + s[tid] - bytes;
+        __syncthreads();
+        if (tid == 255) carry = c + s[255];
+        __syncthreads();
+    }
+    if (tid == 0) offsets[n_jobs] = carry;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* kvtc_last_error(void) { return g_err; }
+
+uint16_t kvtc_host_f16_round_down(float x) { return f16_round_dir(x, false); }
+uint16_t kvtc_host_f16_round_up(float x) { return f16_round_dir(x, true); }
+void kvtc_host_group_header(float lo, float hi, int bits, uint16_t* shift16, uint16_t* scale16) {
+    const GroupQ q = group_header(lo, hi, bits);
+    if (shift16) *shift16 = q.shift16;
+    if (scale16) *scale16 = q.scale16;
+}
+uint32_t kvtc_host_code(float d, uint16_t shift16, uint16_t scale16, int bits) {
+    const float shift = f16_bits_to_f32(shift16);
+    const float sc = f16_bits_to_f32(scale16);
+    const float inv = sc > 0.0f ? 1.0f / sc : 0.0f;
+    const float qmax = (float)((1u << bits) - 1u);
+    volatile float t = d - shift;          // two separate fp32 operations, as in the kernel
+    volatile float q = t * inv;
+    float rq = nearbyintf(q);
+    if (!(rq >= 0.0f)) rq = 0.0f;
+    if (rq > qmax) rq = qmax;
+    return (uint32_t)rq;
+}
+
+kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host, const uint16_t* v_kept_host,
+                             int n_groups, const kvtc_group* groups_host, kvtc_stream stream) {
+    if (out) *out = nullptr;
+    if (!out || !mu_host || !v_kept_host || !groups_host) return fail(KVTC_E_ARG, "kvtc_plan_create: null argument");
+    if (p <= 0 || p % 64 != 0) return fail(KVTC_E_ARG, "kvtc_plan_create: p=%d must be a positive multiple of 64", p);
+    if (r < 16 || r > 1024) return fail(KVTC_E_ARG, "kvtc_plan_create: r=%d outside 16..1024", r);
+    if (n_groups < 1 || n_groups > 64) return fail(KVTC_E_ARG, "kvtc_plan_create: n_groups=%d outside 1..64", n_groups);
+    long sum = 0, payload_bits = 0;
+    for (int g = 0; g < n_groups; ++g) {
+        if (groups_host[g].n < 1) return fail(KVTC_E_ARG, "kvtc_plan_create: group %d is empty", g);
+        if (groups_host[g].bits < 1 || groups_host[g].bits > 16)
+            return fail(KVTC_E_ARG, "kvtc_plan_create: group %d has %d bits (1..16 allowed)", g, groups_host[g].bits);
+        sum += groups_host[g].n;
+        payload_bits += (long)groups_host[g].n * groups_host[g].bits;
+    }
+    if (sum != r) return fail(KVTC_E_ARG, "kvtc_plan_create: group sizes sum to %ld, r=%d", sum, r);
+    for (int g = 0; g < n_groups; ++g)
+        if (groups_host[g].n % 16 != 0)
+            return fail(KVTC_E_UNSUPPORTED, "kvtc_plan_create: group %d has %d coordinates; the kernels need multiples of 16",
+                        g, groups_host[g].n);
+
+    PlanDev d;
+    memset(&d, 0, sizeof(d));
+    d.p = p;
+    d.r = r;
+    d.n_groups = n_groups;
+    d.n_blocks = r / 16;
+    const long total_bits = 32L * n_groups + payload_bits;
+    d.rec_dwords = (int)((total_bits + 31) / 32);
+    const int nt = (r + 31) / 32;
+
+    // encode variant: NTW coordinate tiles per wave, WC waves across coordinates
+    static const int enc_tab[][2] = {{1, 2}, {1, 4}, {1, 6}, {1, 8}, {1, 10}, {2, 6}, {2, 8}, {2, 10}, {4, 6}, {4, 8}};
+    d.enc_wc = 0;
+    for (auto& e : enc_tab)
+        if (e[0] * e[1] >= nt) { d.enc_wc = e[0]; d.enc_ntw = e[1]; break; }
+    static const int dec_tab[][2] = {{2, 2}, {2, 4}, {2, 6}, {2, 8}, {2, 10}, {1, 12}, {1, 16}, {1, 20}, {1, 24}, {1, 32}};
+    d.dec_tt = 0;
+    for (auto& e : dec_tab)
+        if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; break; }
+    if (d.enc_wc == 0 || d.dec_tt == 0) return fail(KVTC_E_UNSUPPORTED, "kvtc_plan_create: no kernel variant for r=%d", r);
+    const int ntp = d.enc_ntw * d.enc_wc;
+    d.enc_tok_wg = 64 * (4 / d.enc_wc);
+    d.dec_tok_wg = 4 * 32 * d.dec_tt;
+    {
+        const int main_b = 2 * 2 * ntp * 1024;
+        const int epi_b = d.enc_tok_wg * (2 * ntp * 8 + n_groups * 8 + (d.rec_dwords + 1) * 4);
+        d.enc_lds = main_b > epi_b ? main_b : epi_b;
+        const int rec_b = d.dec_tok_wg * (d.rec_dwords + 1) * 4;
+        const int slab_b = 2 * 2 * d.dec_nct * 1024;
+        d.dec_lds = rec_b > slab_b ? rec_b : slab_b;
+    }
+    const int lds_cap = kLdsBudget - kJobTableBytes - 64;
+    if (d.enc_lds > lds_cap || d.dec_lds > lds_cap)
+        return fail(KVTC_E_UNSUPPORTED,
+                    "kvtc_plan_create: record of %d bytes with r=%d needs %d/%d bytes of LDS, %d available",
+                    d.rec_dwords * 4, r, d.enc_lds, d.dec_lds, lds_cap);
+
+    // ---- host images ---------------------------------------------------------------
+    const size_t n_venc = (size_t)(p / 16) * ntp * 64 * 8;      // bf16 elements
+    const size_t n_vdec = (size_t)(p / 32) * 2 * d.dec_nct * 64 * 8;
+    std::vector<uint16_t> venc, vdec;
+    std::vector<float> negc, mu;
+    std::vector<uint32_t> blk(64, 0u), grp(n_groups, 0u);
+    try {
+        venc.assign(n_venc, 0);
+        vdec.assign(n_vdec, 0);
+        negc.assign((size_t)32 * ntp, 0.0f);
+        mu.assign(mu_host, mu_host + p);
+    } catch (const std::bad_alloc&) {
+        return fail(KVTC_E_NOMEM, "kvtc_plan_create: host allocation failed");
+    }
+    for (int ks = 0; ks < p / 16; ++ks)
+        for (int ct = 0; ct < ntp; ++ct)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int j = 32 * ct + permuted_index(lane & 31);
+                if (j >= r) continue;
+                uint16_t* dst = &venc[(((size_t)ks * ntp + ct) * 64 + lane) * 8];
+                const int f0 = 16 * ks + 8 * (lane >> 5);
+                for (int e = 0; e < 8; ++e) dst[e] = v_kept_host[(size_t)(f0 + e) * r + j];
+            }
+    for (int ft = 0; ft < p / 32; ++ft)
+        for (int ks = 0; ks < 2 * d.dec_nct; ++ks)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int f = 32 * ft + permuted_index(lane & 31);
+                const int j0 = 32 * (ks >> 1) + 16 * (lane >> 5) + 8 * (ks & 1);
+                uint16_t* dst = &vdec[((((size_t)ft * 2 * d.dec_nct) + ks) * 64 + lane) * 8];
+                for (int e = 0; e < 8; ++e)
+                    if (j0 + e < r) dst[e] = v_kept_host[(size_t)f * r + j0 + e];
+            }
+    for (int j = 0; j < r; ++j) {
+        double c = 0.0;
+        for (int f = 0; f < p; ++f) c += (double)mu_host[f] * (double)bf16_bits_to_float(v_kept_host[(size_t)f * r + j]);
+        negc[j] = -(float)c;
+    }
+    {
+        int b = 0;
+        long pos = 32L * n_groups;       // bit position of the group's first code
+        for (int g = 0; g < n_groups; ++g) {
+            const int nb = groups_host[g].n / 16, bits = groups_host[g].bits;
+            grp[g] = (uint32_t)b | ((uint32_t)nb << 8) | ((uint32_t)bits << 16);
+            for (int k = 0; k < nb; ++k) {
+                blk[b + k] = (uint32_t)bits | ((uint32_t)g << 8) | ((uint32_t)(pos / 16) << 16);
+                pos += 16L * bits;
+            }
+            b += nb;
+        }
+    }
+
+    // ---- one device blob -------------------------------------------------------------
+    size_t off = 0;
+    const size_t o_desc = off;  off = align_up(off + sizeof(PlanDev), 256);
+    const size_t o_venc = off;  off = align_up(off + n_venc * 2, 256);
+    const size_t o_vdec = off;  off = align_up(off + n_vdec * 2, 256);
+    const size_t o_negc = off;  off = align_up(off + negc.size() * 4, 256);
+    const size_t o_mu = off;    off = align_up(off + mu.size() * 4, 256);
+    const size_t o_blk = off;   off = align_up(off + blk.size() * 4, 256);
+    const size_t o_grp = off;   off = align_up(off + grp.size() * 4, 256);
+    char* blob = nullptr;
+    if (hipMalloc(reinterpret_cast<void**>(&blob), off) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(KVTC_E_NOMEM, "kvtc_plan_create: hipMalloc of %zu bytes failed", off);
+    }
+    d.v_enc = reinterpret_cast<const uint4*>(blob + o_venc);
+    d.v_dec = reinterpret_cast<const uint4*>(blob + o_vdec);
+    d.negc = reinterpret_cast<const float*>(blob + o_negc);
+    d.mu = reinterpret_cast<const float*>(blob + o_mu);
+    d.blk = reinterpret_cast<const uint32_t*>(blob + o_blk);
+    d.grp = reinterpret_cast<const uint32_t*>(blob + o_grp);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    auto put = [&](size_t o, const void* src, size_t n) {
+        if (e == hipSuccess) e = hipMemcpyAsync(blob + o, src, n, hipMemcpyHostToDevice, st);
+    };
+    put(o_desc, &d, sizeof(d));
+    put(o_venc, venc.data(), n_venc * 2);
+    put(o_vdec, vdec.data(), n_vdec * 2);
+    put(o_negc, negc.data(), negc.size() * 4);
+    put(o_mu, mu.data(), mu.size() * 4);
+    put(o_blk, blk.data(), blk.size() * 4);
+    put(o_grp, grp.data(), grp.size() * 4);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);    // the host images die with this call
+    if (e != hipSuccess) {
+        (void)hipFree(blob);
+        return fail(KVTC_E_HIP, "kvtc_plan_create: upload failed: %s", hipGetErrorString(e));
+    }
+    kvtc_plan* pl = new (std::nothrow) kvtc_plan;
+    if (!pl) {
+        (void)hipFree(blob);
+        return fail(KVTC_E_NOMEM, "kvtc_plan_create: host allocation failed");
+    }
+    pl->h = d;
+    pl->blob = blob;
+    pl->desc_dev = reinterpret_cast<PlanDev*>(blob + o_desc);
+    pl->record_bytes = (size_t)d.rec_dwords * 4;
+    *out = pl;
+    return KVTC_OK;
+}
+
+void kvtc_plan_destroy(kvtc_plan* plan) {
+    if (!plan) return;
+    (void)hipFree(plan->blob);
+    delete plan;
+}
+
+size_t kvtc_record_bytes(const kvtc_plan* plan) { return plan ? plan->record_bytes : 0; }
+
+size_t kvtc_encoded_bytes(const kvtc_plan* plan, int64_t n_tokens) {
+    return (plan && n_tokens > 0) ? plan->record_bytes * (size_t)n_tokens : 0;
+}
+
+static kvtc_status check_x(const char* who, const void* x, kvtc_dtype dtype, int64_t ld_x, int p) {
+    if (!dtype_ok(dtype)) return fail(KVTC_E_ARG, "%s: unknown dtype %d", who, (int)dtype);
+    if (ld_x < p) return fail(KVTC_E_ARG, "%s: ld_x=%lld < p=%d", who, (long long)ld_x, p);
+    if ((reinterpret_cast<uintptr_t>(x) & 15u) || ((size_t)ld_x * elem_size(dtype)) % 16 != 0)
+        return fail(KVTC_E_ARG, "%s: feature array base and row pitch must be 16-byte aligned", who);
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int64_t ld_x,
+                        void* out_dev, size_t out_cap, kvtc_stream stream) {
+    if (!plan) return fail(KVTC_E_ARG, "kvtc_encode: null plan");
+    if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_encode: n_tokens=%lld", (long long)n_tokens);
+    if (n_tokens == 0) return KVTC_OK;
+    if (!x_dev || !out_dev) return fail(KVTC_E_ARG, "kvtc_encode: null buffer");
+    kvtc_status st = check_x("kvtc_encode", x_dev, dtype, ld_x, plan->h.p);
+    if (st != KVTC_OK) return st;
+    if (reinterpret_cast<uintptr_t>(out_dev) & 15u) return fail(KVTC_E_ARG, "kvtc_encode: out_dev must be 16-byte aligned");
+    if (out_cap < plan->record_bytes * (size_t)n_tokens)
+        return fail(KVTC_E_SMALL, "kvtc_encode: out_cap=%zu < %zu", out_cap, plan->record_bytes * (size_t)n_tokens);
+    KernelArgs a;
+    memset(&a, 0, sizeof(a));
+    a.plans = plan->desc_dev;
+    a.n_plans = 1;
+    a.jobs = nullptr;
+    a.n_jobs = 1;
+    a.single = kvtc_job{0, (int32_t)n_tokens, 0};
+    a.offsets = nullptr;
+    a.x = x_dev;
+    a.ld_x = ld_x;
+    a.stream_buf = out_dev;
+    a.cap = out_cap;
+    a.status = nullptr;
+    const int64_t tiles = (n_tokens + plan->h.enc_tok_wg - 1) / plan->h.enc_tok_wg;
+    const int grid = (int)(tiles < cu_count() ? tiles : cu_count());
+    hipError_t e = launch_encode(a, dtype, grid, (size_t)kJobTableBytes + 64 + plan->h.enc_lds, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode: launch failed: %s", hipGetErrorString(e));
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens, void* x_out_dev,
+                        kvtc_dtype dtype, int64_t ld_x, kvtc_stream stream) {
+    if (!plan) return fail(KVTC_E_ARG, "kvtc_decode: null plan");
+    if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_decode: n_tokens=%lld", (long long)n_tokens);
+    if (n_tokens == 0) return KVTC_OK;
+    if (!in_dev || !x_out_dev) return fail(KVTC_E_ARG, "kvtc_decode: null buffer");
+    kvtc_status st = check_x("kvtc_decode", x_out_dev, dtype, ld_x, plan->h.p);
+    if (st != KVTC_OK) return st;
+    if (reinterpret_cast<uintptr_t>(in_dev) & 15u) return fail(KVTC_E_ARG, "kvtc_decode: in_dev must be 16-byte aligned");
+    if (in_bytes < plan->record_bytes * (size_t)n_tokens)
+        return fail(KVTC_E_SMALL, "kvtc_decode: in_bytes=%zu < %zu", in_bytes, plan->record_bytes * (size_t)n_tokens);
+    KernelArgs a;
+    memset(&a, 0, sizeof(a));
+    a.plans = plan->desc_dev;
+    a.n_plans = 1;
+    a.n_jobs = 1;
+    a.single = kvtc_job{0, (int32_t)n_tokens, 0};
+    a.x = x_out_dev;
+    a.ld_x = ld_x;
+    a.stream_buf = const_cast<void*>(in_dev);
+    a.cap = in_bytes;
+    const int64_t tiles = (n_tokens + plan->h.dec_tok_wg - 1) / plan->h.dec_tok_wg;
+    const int grid = (int)(tiles < cu_count() ? tiles : cu_count());
+    hipError_t e = launch_decode(a, dtype, grid, (size_t)kJobTableBytes + 64 + plan->h.dec_lds, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode: launch failed: %s", hipGetErrorString(e));
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, int n_plans, kvtc_stream stream) {
+    if (out) *out = nullptr;
+    if (!out || !plans || n_plans < 1) return fail(KVTC_E_ARG, "kvtc_batch_create: null argument or no plans");
+    std::vector<PlanDev> h;
+    kvtc_batch* b = new (std::nothrow) kvtc_batch;
+    if (!b) return fail(KVTC_E_NOMEM, "kvtc_batch_create: host allocation failed");
+    b->plans_dev = nullptr;
+    b->rec_dwords_dev = nullptr;
+    b->n_plans = n_plans;
+    b->enc_lds = b->dec_lds = 0;
+    for (int i = 0; i < n_plans; ++i) {
+        if (!plans[i]) {
+            delete b;
+            return fail(KVTC_E_ARG, "kvtc_batch_create: plan %d is null", i);
+        }
+        h.push_back(plans[i]->h);
+        b->rec_dwords.push_back(plans[i]->h.rec_dwords);
+        if (plans[i]->h.enc_lds > b->enc_lds) b->enc_lds = plans[i]->h.enc_lds;
+        if (plans[i]->h.dec_lds > b->dec_lds) b->dec_lds = plans[i]->h.dec_lds;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&b->plans_dev), sizeof(PlanDev) * n_plans);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&b->rec_dwords_dev), sizeof(uint32_t) * n_plans);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        kvtc_batch_destroy(b);
+        return fail(KVTC_E_NOMEM, "kvtc_batch_create: hipMalloc failed");
+    }
+    e = hipMemcpyAsync(b->plans_dev, h.data(), sizeof(PlanDev) * n_plans, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(b->rec_dwords_dev, b->rec_dwords.data(), sizeof(uint32_t) * n_plans, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) {
+        kvtc_batch_destroy(b);
+        return fail(KVTC_E_HIP, "kvtc_batch_create: upload failed: %s", hipGetErrorString(e));
+    }
+    *out = b;
+    return KVTC_OK;
+}
+
+void kvtc_batch_destroy(kvtc_batch* batch) {
+    if (!batch) return;
+    if (batch->plans_dev) (void)hipFree(batch->plans_dev);
+    if (batch->rec_dwords_dev) (void)hipFree(batch->rec_dwords_dev);
+    delete batch;
+}
+
+kvtc_status kvtc_offsets(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs, uint64_t* offsets_dev,
+                         kvtc_stream stream) {
+    if (!batch || !offsets_dev || n_jobs < 0 || (n_jobs > 0 && !jobs_dev))
+        return fail(KVTC_E_ARG, "kvtc_offsets: null argument or negative job count");
+    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), batch->rec_dwords_dev,
+                       batch->n_plans, jobs_dev, n_jobs, offsets_dev);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_offsets: launch failed: %s", hipGetErrorString(e));
+    return KVTC_OK;
+}
+
+static kvtc_status batch_common(const char* who, const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs,
+                                const void* x, kvtc_dtype dtype, int64_t ld_x, const uint64_t* offsets_dev,
+                                const void* stream_buf, const uint32_t* status_dev, bool* nothing) {
+    *nothing = false;
+    if (!batch) return fail(KVTC_E_ARG, "%s: null batch", who);
+    if (n_jobs < 0) return fail(KVTC_E_ARG, "%s: n_jobs=%d", who, n_jobs);
+    if (n_jobs == 0) { *nothing = true; return KVTC_OK; }
+    if (n_jobs > kMaxJobs) return fail(KVTC_E_UNSUPPORTED, "%s: %d jobs, at most %d per call", who, n_jobs, kMaxJobs);
+    if (!jobs_dev || !x || !offsets_dev || !stream_buf || !status_dev) return fail(KVTC_E_ARG, "%s: null buffer", who);
+    if (!dtype_ok(dtype)) return fail(KVTC_E_ARG, "%s: unknown dtype %d", who, (int)dtype);
+    if ((reinterpret_cast<uintptr_t>(x) & 15u) || ((size_t)ld_x * elem_size(dtype)) % 16 != 0 || ld_x <= 0)
+        return fail(KVTC_E_ARG, "%s: feature array base and row pitch must be 16-byte aligned", who);
+    if (reinterpret_cast<uintptr_t>(stream_buf) & 15u) return fail(KVTC_E_ARG, "%s: stream buffer must be 16-byte aligned", who);
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_encode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs, const void* x_base_dev,
+                              kvtc_dtype dtype, int64_t ld_x, const uint64_t* offsets_dev, void* out_base_dev,
+                              size_t out_cap, uint32_t* status_dev, kvtc_stream stream) {
+    bool nothing;
+    kvtc_status st = batch_common("kvtc_encode_batch", batch, jobs_dev, n_jobs, x_base_dev, dtype, ld_x, offsets_dev,
+                                  out_base_dev, status_dev, &nothing);
+    if (st != KVTC_OK || nothing) return st;
+    KernelArgs a;
+    memset(&a, 0, sizeof(a));
+    a.plans = batch->plans_dev;
+    a.n_plans = batch->n_plans;
+    a.jobs = jobs_dev;
+    a.n_jobs = n_jobs;
+    a.offsets = offsets_dev;
+    a.x = x_base_dev;
+    a.ld_x = ld_x;
+    a.stream_buf = out_base_dev;
+    a.cap = out_cap;
+    a.status = status_dev;
+    hipError_t e = launch_encode(a, dtype, cu_count(), (size_t)kJobTableBytes + 64 + batch->enc_lds, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode_batch: launch failed: %s", hipGetErrorString(e));
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs, const void* in_base_dev,
+                              size_t in_bytes, const uint64_t* offsets_dev, void* x_out_base_dev, kvtc_dtype dtype,
+                              int64_t ld_x, uint32_t* status_dev, kvtc_stream stream) {
+    bool nothing;
+    kvtc_status st = batch_common("kvtc_decode_batch", batch, jobs_dev, n_jobs, x_out_base_dev, dtype, ld_x, offsets_dev,
+                                  in_base_dev, status_dev, &nothing);
+    if (st != KVTC_OK || nothing) return st;
+    KernelArgs a;
+    memset(&a, 0, sizeof(a));
+    a.plans = batch->plans_dev;
+    a.n_plans = batch->n_plans;
+    a.jobs = jobs_dev;
+    a.n_jobs = n_jobs;
+    a.offsets = offsets_dev;
+    a.x = x_out_base_dev;
+    a.ld_x = ld_x;
+    a.stream_buf = const_cast<void*>(in_base_dev);
+    a.cap = in_bytes;
+    a.status = status_dev;
+    hipError_t e = launch_decode(a, dtype, cu_count(), (size_t)kJobTableBytes + 64 + batch->dec_lds, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode_batch: launch failed: %s", hipGetErrorString(e));
+    return KVTC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,251 @@
+// Fused decode kernel for gfx950, the mirror of the encode kernel: records are unpacked
+// and dequantised straight into bf16 matrix-core operands, back-projected with V_kept and
+// un-centred, one launch.  (Paper, Section "Method", mode "Decompression"; eq. 3.)
+//
+// X_hat^T = V_kept D_hat^T with the 32x32x16 bf16 MFMA: M = features, N = tokens,
+// K = kept coordinates.  A lane owns one token; its dequantised coordinates ARE its B operand
+// (16 consecutive coordinates = one block of the record = two k-step fragments), so they are
+// built once per tile and stay in registers while the wave sweeps the feature tiles.
+// V_kept is pre-swizzled into A fragments per 32-feature tile, staged through LDS
+// (double-buffered) and shared by the four wavefronts.  Rows of the A operand are permuted
+// so that a lane ends up with 16 consecutive features of its token: 32 contiguous bytes of
+// bf16 output per store pair.
+#include <hip/hip_runtime.h>
+#include "kvtc_dev.h"
+#include "kvtc_numeric.h"
+
+namespace kvtc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ bf16x8 as_bf16x8_d(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+template <typename OT> struct OutStore;
+template <> struct OutStore<uint16_t> {
+    static __device__ __forceinline__ void store(uint16_t* p, const f32x16& v) {
+        uint4 a, b;
+        a.x = pack_bf16x2(v[0], v[1]);   a.y = pack_bf16x2(v[2], v[3]);
+        a.z = pack_bf16x2(v[4], v[5]);   a.w = pack_bf16x2(v[6], v[7]);
+        b.x = pack_bf16x2(v[8], v[9]);   b.y = pack_bf16x2(v[10], v[11]);
+        b.z = pack_bf16x2(v[12], v[13]); b.w = pack_bf16x2(v[14], v[15]);
+        reinterpret_cast<uint4*>(p)[0] = a;
+        reinterpret_cast<uint4*>(p)[1] = b;
+    }
+};
+template <> struct OutStore<float> {
+    static __device__ __forceinline__ void store(float* p, const f32x16& v) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            reinterpret_cast<float4*>(p)[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    }
+};
+
+template <int NCT, int TT, typename OT>
+__device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const TileRef& tr,
+                                            const KernelArgs& a, uint4* smem) {
+    constexpr int TOK_W = 32 * TT;
+    constexpr int TOK_WG = 4 * TOK_W;
+    constexpr int SLAB_U4 = 2 * NCT * 64;          // one 32-feature tile of V_kept
+    constexpr int NST = (SLAB_U4 + kThreads - 1) / kThreads;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int p = P->p;
+    const int T = tr.n_tokens;
+    const int tok_tile0 = tr.tile * TOK_WG;
+    const int rd = P->rec_dwords;
+    const int rstride = rd + 1;
+
+    // ---- records -> LDS (coalesced), then each lane unpacks its blocks ---------------
+    uint32_t* rec = reinterpret_cast<uint32_t*>(smem);
+    {
+        const int n_valid = min(TOK_WG, T - tok_tile0);
+        const uint32_t* in = reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(a.stream_buf) + tr.offset) +
+                             (size_t)tok_tile0 * rd;
+        const uint32_t magic = 0xffffffffu / (uint32_t)rd + 1u;
+        const int total = n_valid * rd;
+        for (int i = tid; i < total; i += kThreads) {
+            const uint32_t t = __umulhi((uint32_t)i, magic);
+            rec[t * rstride + ((uint32_t)i - t * rd)] = in[i];
+        }
+        // rows of tokens past the end of the tensor and the pad dwords: defined contents
+        for (int i = tid; i < TOK_WG; i += kThreads) rec[i * rstride + rd] = 0u;
+        for (int i = total + tid; i < TOK_WG * rd; i += kThreads) {
+            const uint32_t t = __umulhi((uint32_t)i, magic);
+            rec[t * rstride + ((uint32_t)i - t * rd)] = 0u;
+        }
+    }
+    __syncthreads();
+
+    bf16x8 bop[TT][2 * NCT];
+#pragma unroll
+    for (int c = 0; c < NCT; ++c) {
+        const uint32_t info = P->blk[2 * c + h];
+        const uint32_t bits = info & 0xffu;
+        const uint32_t g = (info >> 8) & 0xffu;
+        const uint32_t pos0 = (info >> 16) * 16u;
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            float d[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) d[i] = 0.0f;
+            if (bits != 0u) {
+                const uint32_t* row = rec + (wave * TOK_W + tt * 32 + l32) * rstride;
+                const uint32_t hdr = row[g];
+                const float shift = f16_bits_to_f32((uint16_t)(hdr & 0xffffu));
+                const float scale = f16_bits_to_f32((uint16_t)(hdr >> 16));
+                if (bits <= 8u) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const uint32_t pos = pos0 + 4u * k * bits;
+                        const uint32_t dw = pos >> 5;
+                        const uint32_t w = __builtin_amdgcn_alignbit(row[dw + 1], row[dw], pos & 31u);
+#pragma unroll
+                        for (int m = 0; m < 4; ++m) {
+                            const uint32_t code = __builtin_amdgcn_ubfe(w, m * bits, bits);
+                            d[4 * k + m] = __fmaf_rn((float)code, scale, shift);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const uint32_t pos = pos0 + 2u * k * bits;
+                        const uint32_t dw = pos >> 5;
+                        const uint32_t w = __builtin_amdgcn_alignbit(row[dw + 1], row[dw], pos & 31u);
+#pragma unroll
+                        for (int m = 0; m < 2; ++m) {
+                            const uint32_t code = __builtin_amdgcn_ubfe(w, m * bits, bits);
+                            d[2 * k + m] = __fmaf_rn((float)code, scale, shift);
+                        }
+                    }
+                }
+            }
+            bf16x8 f0, f1;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { f0[i] = (__bf16)d[i]; f1[i] = (__bf16)d[8 + i]; }
+            bop[tt][2 * c] = f0;
+            bop[tt][2 * c + 1] = f1;
+        }
+    }
+    __syncthreads();          // record image is dead; the slabs reuse its space
+
+    // ---- sweep the feature tiles --------------------------------------------------------
+    uint4* slab0 = smem;
+    uint4* slab1 = smem + SLAB_U4;
+    const uint4* vg = P->v_dec;
+    const int n_ft = p / 32;
+    uint4 stage[NST];
+#pragma unroll
+    for (int i = 0; i < NST; ++i) {
+        const int idx = tid + i * kThreads;
+        if (idx < SLAB_U4) stage[i] = vg[idx];
+    }
+#pragma unroll
+    for (int i = 0; i < NST; ++i) {
+        const int idx = tid + i * kThreads;
+        if (idx < SLAB_U4) slab0[idx] = stage[i];
+    }
+    __syncthreads();
+
+    OT* orow[TT];
+    bool valid[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        const int t = tok_tile0 + wave * TOK_W + tt * 32 + l32;
+        valid[tt] = t < T;
+        orow[tt] = reinterpret_cast<OT*>(const_cast<void*>(a.x)) + (tr.x_row0 + (valid[tt] ? t : 0)) * a.ld_x + 16 * h;
+    }
+    const float* mu = P->mu + 16 * h;
+
+    for (int ft = 0; ft < n_ft; ++ft) {
+        const uint4* cur = (ft & 1) ? slab1 : slab0;
+        uint4* nxt = (ft & 1) ? slab0 : slab1;
+        const bool more = ft + 1 < n_ft;
+        if (more) {
+            const uint4* src = vg + (size_t)(ft + 1) * SLAB_U4;
+#pragma unroll
+            for (int i = 0; i < NST; ++i) {
+                const int idx = tid + i * kThreads;
+                if (idx < SLAB_U4) stage[i] = src[idx];
+            }
+        }
+        f32x16 acc[TT];
+        {
+            f32x16 m;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = *reinterpret_cast<const float4*>(mu + ft * 32 + 4 * q);
+                m[4 * q] = v.x; m[4 * q + 1] = v.y; m[4 * q + 2] = v.z; m[4 * q + 3] = v.w;
+            }
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) acc[tt] = m;
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2 * NCT; ++ks) {
+            const bf16x8 av = as_bf16x8_d(cur[ks * 64 + lane]);
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+                acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bop[tt][ks], acc[tt], 0, 0, 0);
+        }
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+            if (valid[tt]) OutStore<OT>::store(orow[tt] + ft * 32, acc[tt]);
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < NST; ++i) {
+                const int idx = tid + i * kThreads;
+                if (idx < SLAB_U4) nxt[idx] = stage[i];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <typename OT>
+__global__ void __launch_bounds__(kThreads) kvtc_decode_kernel(const KernelArgs a) {
+    extern __shared__ uint4 smem[];
+    uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
+    uint4* work = smem + kJobTableBytes / 16 + 1;
+    const uint32_t total = build_tile_table<false>(a, tile_start, reinterpret_cast<uint32_t*>(work));
+    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
+        const TileRef tr = find_tile(a, tile_start, tile);
+        const PlanDev* P = a.plans + tr.plan;
+        const int key = __builtin_amdgcn_readfirstlane(P->dec_tt * 100 + P->dec_nct);
+        switch (key) {
+#define KVTC_CASE(TT, NCT) case (TT) * 100 + (NCT): decode_tile<NCT, TT, OT>(P, tr, a, work); break;
+            KVTC_CASE(2, 2) KVTC_CASE(2, 4) KVTC_CASE(2, 6) KVTC_CASE(2, 8) KVTC_CASE(2, 10)
+            KVTC_CASE(1, 12) KVTC_CASE(1, 16) KVTC_CASE(1, 20) KVTC_CASE(1, 24) KVTC_CASE(1, 32)
+#undef KVTC_CASE
+            default: break;
+        }
+    }
+}
+
+hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int grid, size_t lds_bytes, hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kvtc_decode_kernel<uint16_t>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kvtc_decode_kernel<float>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (dtype == KVTC_BF16)
+        hipLaunchKernelGGL(kvtc_decode_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+    else
+        hipLaunchKernelGGL(kvtc_decode_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace kvtc

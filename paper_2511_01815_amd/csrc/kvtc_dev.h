@@ -1,0 +1,137 @@
+// Device-side descriptors and the job -> tile scheduling shared by the encode and
+// decode kernels.  Internal to the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/kvtc.h"
+
+namespace kvtc {
+
+constexpr int kThreads = 256;          // 4 wavefronts, one per SIMD of a compute unit
+constexpr int kMaxJobs = 2048;         // jobs per batched launch (tile table lives in LDS)
+constexpr int kLdsBudget = 160 * 1024; // gfx950 LDS per workgroup
+constexpr int kJobTableBytes = (kMaxJobs + 1) * 4;
+
+// Everything a kernel needs to know about a plan.  Lives in device memory and is read
+// through wave-uniform (scalar) loads.
+struct PlanDev {
+    int32_t p, r, n_groups, n_blocks;       // n_blocks = r / 16
+    int32_t rec_dwords;                     // R / 4
+    int32_t enc_ntw, enc_wc;                // encode variant: coefficient tiles per wave, waves across coefficients
+    int32_t dec_nct, dec_tt;                // decode variant: coefficient tiles, token tiles per wave
+    int32_t enc_tok_wg, dec_tok_wg;         // tokens per workgroup tile
+    int32_t enc_lds, dec_lds;               // dynamic LDS bytes needed (without the job table)
+    int32_t pad_;
+    const uint4* v_enc;    // [p/16][32*ntp/32][64] MFMA A fragments of V_kept^T (encode)
+    const uint4* v_dec;    // [p/32][2*nct][64]     MFMA A fragments of V_kept   (decode)
+    const float* negc;     // [32*ntp]  -(mu^T V_kept), zero in the padding
+    const float* mu;       // [p]
+    const uint32_t* blk;   // [64] per 16-coordinate block: bits | group << 8 | halfword offset << 16; 0 = padding
+    const uint32_t* grp;   // [n_groups] first block | n blocks << 8 | bits << 16
+};
+
+struct KernelArgs {
+    const PlanDev* plans;      // device array
+    int32_t n_plans;
+    const kvtc_job* jobs;      // device array, or nullptr -> `single`
+    int32_t n_jobs;
+    kvtc_job single;
+    const uint64_t* offsets;   // device, [n_jobs + 1], or nullptr (single job at offset 0)
+    const void* x;             // feature array (encode: input, decode: output)
+    int64_t ld_x;
+    void* stream_buf;          // record stream (encode: output, decode: input)
+    uint64_t cap;              // bytes available in stream_buf
+    uint32_t* status;          // device, may be nullptr
+};
+
+struct TileRef {
+    int32_t job, plan, n_tokens;
+    int64_t x_row0;
+    uint64_t offset;
+    int32_t tile;      // tile index inside the job
+};
+
+// Builds the exclusive prefix of tiles per job in LDS (tile_start[0..n_jobs]) and returns
+// the total.  A job with a bad plan index, a negative token count or a stream that would end
+// beyond `cap` gets zero tiles; workgroup 0 reports the lowest such job in *status.
+template <bool kEncode>
+__device__ inline uint32_t build_tile_table(const KernelArgs& a, uint32_t* tile_start, uint32_t* scratch /*[kThreads + 1]*/) {
+    const int tid = threadIdx.x;
+    const int n_jobs = a.jobs ? a.n_jobs : 1;
+    const int per = (n_jobs + kThreads - 1) / kThreads;
+    const int j0 = tid * per;
+    uint32_t local[kMaxJobs / kThreads];
+    uint32_t sum = 0;
+    uint32_t first_bad = 0xffffffffu;
+#pragma unroll
+    for (int k = 0; k < kMaxJobs / kThreads; ++k) {
+        uint32_t tiles = 0;
+        const int j = j0 + k;
+        if (k < per && j < n_jobs) {
+            const kvtc_job jb = a.jobs ? a.jobs[j] : a.single;
+            bool ok = jb.plan >= 0 && jb.plan < a.n_plans && jb.n_tokens >= 0;
+            if (ok && a.offsets) ok = a.offsets[j + 1] <= a.cap && a.offsets[j + 1] >= a.offsets[j];
+            if (ok) {
+                const int tw = kEncode ? a.plans[jb.plan].enc_tok_wg : a.plans[jb.plan].dec_tok_wg;
+                tiles = (uint32_t)((jb.n_tokens + tw - 1) / tw);
+            } else if (first_bad == 0xffffffffu) {
+                first_bad = (uint32_t)j;
+            }
+        }
+        local[k] = tiles;
+        sum += tiles;
+    }
+    // exclusive scan of the per-thread sums
+    scratch[tid] = sum;
+    __syncthreads();
+    for (int d = 1; d < kThreads; d <<= 1) {
+        uint32_t v = tid >= d ? scratch[tid - d] : 0u;
+        __syncthreads();
+        scratch[tid] += v;
+        __syncthreads();
+    }
+    uint32_t run = scratch[tid] - sum;
+    const uint32_t total = scratch[kThreads - 1];
+#pragma unroll
+    for (int k = 0; k < kMaxJobs / kThreads; ++k) {
+        const int j = j0 + k;
+        if (k < per && j < n_jobs) tile_start[j] = run;
+        run += local[k];
+    }
+    if (tid == 0) tile_start[n_jobs] = total;
+    __syncthreads();
+    // lowest bad job -> status (workgroup 0 only; a plain vector store)
+    if (a.status && blockIdx.x == 0) {
+        scratch[tid] = first_bad;
+        __syncthreads();
+        for (int d = kThreads / 2; d > 0; d >>= 1) {
+            if (tid < d) scratch[tid] = min(scratch[tid], scratch[tid + d]);
+            __syncthreads();
+        }
+        if (tid == 0 && scratch[0] != 0xffffffffu) *a.status = scratch[0] + 1u;
+    }
+    __syncthreads();
+    return total;
+}
+
+__device__ inline TileRef find_tile(const KernelArgs& a, const uint32_t* tile_start, uint32_t tile) {
+    const int n_jobs = a.jobs ? a.n_jobs : 1;
+    int lo = 0, hi = n_jobs;                 // invariant: tile_start[lo] <= tile < tile_start[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tile_start[mid] <= tile) lo = mid; else hi = mid;
+    }
+    lo = __builtin_amdgcn_readfirstlane(lo);
+    const kvtc_job jb = a.jobs ? a.jobs[lo] : a.single;
+    TileRef t;
+    t.job = lo;
+    t.plan = __builtin_amdgcn_readfirstlane(jb.plan);
+    t.n_tokens = __builtin_amdgcn_readfirstlane(jb.n_tokens);
+    t.x_row0 = jb.x_row0;
+    t.offset = a.offsets ? a.offsets[lo] : 0ull;
+    t.tile = (int32_t)(tile - tile_start[lo]);
+    t.tile = __builtin_amdgcn_readfirstlane(t.tile);
+    return t;
+}
+
+}  // namespace kvtc

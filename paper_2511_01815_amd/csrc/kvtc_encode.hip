@@ -1,0 +1,308 @@
+// Fused encode kernel for gfx950: projection onto the kept PCA basis on the bf16 matrix
+// cores, then per-token group min-max quantisation and bit-packing, one launch.
+// (Paper, Section "Method", mode "Compression"; Sections "Feature decorrelation" and
+// "Quantization".)
+//
+// Work decomposition.  A workgroup is 4 wavefronts (one per SIMD, up to 512 registers each)
+// and owns a tile of tokens and ALL kept coordinates of those tokens, because a group's
+// min/max needs every coordinate of the group before any of its codes exists.
+// The product is computed transposed, D^T = V_kept^T X^T, with the 32x32x16 bf16 MFMA:
+// M = coordinates, N = tokens, K = features.  Then a lane owns one token (column) and, by
+// permuting the rows of the A operand, 16 *consecutive* coordinates of it per 32-coordinate
+// tile -- exactly one 16-coordinate block of the record format, so quantisation and packing
+// are lane-local with static bit offsets.
+//   * X is read straight from HBM into the B operand registers (a lane reads 16 contiguous
+//     bytes of its token's row per k-step); every byte of X is read once.
+//   * V_kept is pre-swizzled at plan creation into A-operand fragments; slabs of it are
+//     staged through LDS (double-buffered) and shared by the wavefronts of the workgroup.
+//   * For wide plans the coordinates are split over WC wavefronts that share the tokens.
+// Epilogue: block min/max -> LDS -> per (token, group) header (fp16 shift down, scale up)
+// -> codes -> OR-ed into the record image in LDS -> one contiguous, coalesced store of the
+// tile's records.
+#include <hip/hip_runtime.h>
+#include "kvtc_dev.h"
+#include "kvtc_numeric.h"
+
+namespace kvtc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// 8 consecutive features of one token as a B-operand fragment.
+template <typename XT> struct XFrag;
+template <> struct XFrag<uint16_t> {       // bf16 input
+    uint4 v;
+    __device__ __forceinline__ void load(const uint16_t* p) { v = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ bf16x8 get() const { return as_bf16x8(v); }
+};
+template <> struct XFrag<float> {          // fp32 input, rounded to bf16 (nearest even) on use
+    float4 a, b;
+    __device__ __forceinline__ void load(const float* p) {
+        a = *reinterpret_cast<const float4*>(p);
+        b = *reinterpret_cast<const float4*>(p + 4);
+    }
+    __device__ __forceinline__ bf16x8 get() const {
+        bf16x8 r;
+        r[0] = (__bf16)a.x; r[1] = (__bf16)a.y; r[2] = (__bf16)a.z; r[3] = (__bf16)a.w;
+        r[4] = (__bf16)b.x; r[5] = (__bf16)b.y; r[6] = (__bf16)b.z; r[7] = (__bf16)b.w;
+        return r;
+    }
+};
+
+// OR `len` bits of v into the record image at bit position pos (pos, len per lane).
+__device__ __forceinline__ void put_bits(uint32_t* rec, uint32_t pos, uint32_t v, uint32_t len) {
+    const uint32_t dw = pos >> 5, s = pos & 31u;
+    atomicOr(rec + dw, v << s);
+    if (s + len > 32u) atomicOr(rec + dw + 1, v >> (32u - s));
+}
+
+template <int NTW, int WC, typename XT>
+__device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const TileRef& tr,
+                                            const KernelArgs& a, uint4* smem) {
+    constexpr int TT = 2;                    // token tiles (of 32) per wave
+    constexpr int NTP = NTW * WC;            // coordinate tiles of the padded plan
+    constexpr int WT = 4 / WC;               // waves across tokens
+    constexpr int TOK_WG = 64 * WT;
+    constexpr int KS = 2;                    // k-steps (16 features) per LDS slab
+    constexpr int SLAB_U4 = KS * NTP * 64;
+    constexpr int NST = (SLAB_U4 + kThreads - 1) / kThreads;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wc = wave % WC, wt = wave / WC;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int p = P->p;
+    const int T = tr.n_tokens;
+    const int tok_tile0 = tr.tile * TOK_WG;
+
+    // ---- operands ---------------------------------------------------------------
+    const XT* xrow[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        int t = tok_tile0 + wt * 64 + tt * 32 + l32;
+        t = t < T ? t : T - 1;                                   // tail: re-read the last row
+        xrow[tt] = reinterpret_cast<const XT*>(a.x) + (tr.x_row0 + t) * a.ld_x + 8 * h;
+    }
+    f32x16 acc[TT][NTW];
+    {
+        const float* negc = P->negc + (wc * NTW) * 32 + 16 * h;
+#pragma unroll
+        for (int ct = 0; ct < NTW; ++ct) {
+            f32x16 c;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = *reinterpret_cast<const float4*>(negc + ct * 32 + 4 * q);
+                c[4 * q] = v.x; c[4 * q + 1] = v.y; c[4 * q + 2] = v.z; c[4 * q + 3] = v.w;
+            }
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) acc[tt][ct] = c;
+        }
+    }
+
+    uint4* slab0 = smem;
+    uint4* slab1 = smem + SLAB_U4;
+    const uint4* vg = P->v_enc;
+    const int n_slabs = p / (16 * KS);          // even: p is a multiple of 64
+    static_assert(SLAB_U4 % kThreads == 0, "slab copy assumes whole rounds of the workgroup");
+
+    uint4 stage[NST];
+    XFrag<XT> xa[TT][KS], xb[TT][KS];
+
+    // prologue: slab 0 -> LDS, first X batch -> registers
+#pragma unroll
+    for (int i = 0; i < NST; ++i) stage[i] = vg[tid + i * kThreads];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xa[tt][ks].load(xrow[tt] + ks * 16);
+#pragma unroll
+    for (int i = 0; i < NST; ++i) slab0[tid + i * kThreads] = stage[i];
+    __syncthreads();
+
+    // One slab step: issue the global loads of the next slab and X batch, run the
+    // 2*KS*NTW MFMAs of this slab with the A fragments read from LDS two steps ahead,
+    // then park the next slab in the other LDS buffer.
+    auto slab_step = [&](const uint4* cur, uint4* nxt, XFrag<XT> (&xc)[TT][KS], XFrag<XT> (&xn)[TT][KS], int s) {
+        const bool more = s + 1 < n_slabs;
+        if (more) {
+            const uint4* src = vg + (size_t)(s + 1) * SLAB_U4;
+#pragma unroll
+            for (int i = 0; i < NST; ++i) stage[i] = src[tid + i * kThreads];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) xn[tt][ks].load(xrow[tt] + (s + 1) * KS * 16 + ks * 16);
+        }
+        constexpr int NSTEP = KS * NTW;
+        bf16x8 xv[TT][KS];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) xv[tt][ks] = xc[tt][ks].get();
+        const uint4* abase = cur + (wc * NTW) * 64 + lane;
+        uint4 af[3];
+        af[0] = abase[0];
+        if (NSTEP > 1) af[1] = abase[((1 / NTW) * NTP + (1 % NTW)) * 64];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < NSTEP; ++j) {
+            const int ks = j / NTW, ct = j % NTW;
+            if (j + 2 < NSTEP) af[(j + 2) % 3] = abase[(((j + 2) / NTW) * NTP + ((j + 2) % NTW)) * 64];
+            const bf16x8 av = as_bf16x8(af[j % 3]);
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+                acc[tt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, xv[tt][ks], acc[tt][ct], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < NST; ++i) nxt[tid + i * kThreads] = stage[i];
+        }
+        __syncthreads();
+    };
+    for (int s = 0; s < n_slabs; s += 2) {
+        slab_step(slab0, slab1, xa, xb, s);
+        slab_step(slab1, slab0, xb, xa, s + 1);
+    }
+
+    // ---- epilogue -----------------------------------------------------------------
+    // LDS: mm[2*NTP][TOK_WG] float2 | gq[G][TOK_WG] float2 | rec[TOK_WG][rd + 1] dwords
+    const int G = P->n_groups;
+    const int rd = P->rec_dwords;
+    const int rstride = rd + 1;                 // odd-ish pitch keeps lanes on distinct banks
+    float2* mm = reinterpret_cast<float2*>(smem);
+    float2* gq = mm + 2 * NTP * TOK_WG;
+    uint32_t* rec = reinterpret_cast<uint32_t*>(gq + G * TOK_WG);
+
+    // A: block min/max, and clear the record image
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        const int tw = wt * 64 + tt * 32 + l32;
+#pragma unroll
+        for (int ct = 0; ct < NTW; ++ct) {
+            const f32x16& d = acc[tt][ct];
+            float lo = d[0], hi = d[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) { lo = fminf(lo, d[i]); hi = fmaxf(hi, d[i]); }
+            mm[(2 * (wc * NTW + ct) + h) * TOK_WG + tw] = make_float2(lo, hi);
+            __builtin_amdgcn_sched_barrier(0);      // keep the accumulator reads from piling up
+        }
+    }
+    for (int i = tid; i < TOK_WG * rstride; i += kThreads) rec[i] = 0u;
+    __syncthreads();
+
+    // B: one header per (token, group)
+    for (int item = tid; item < TOK_WG * G; item += kThreads) {
+        const int tw = item % TOK_WG, g = item / TOK_WG;
+        const uint32_t gi = P->grp[g];
+        const int b0 = gi & 0xff, nb = (gi >> 8) & 0xff, bits = (gi >> 16) & 0xff;
+        float lo = __builtin_inff(), hi = -__builtin_inff();
+        for (int k = 0; k < nb; ++k) {
+            const float2 m = mm[(b0 + k) * TOK_WG + tw];
+            lo = fminf(lo, m.x);
+            hi = fmaxf(hi, m.y);
+        }
+        const GroupQ q = group_header(lo, hi, bits);
+        gq[g * TOK_WG + tw] = make_float2(q.shift, q.inv);
+        rec[tw * rstride + g] = (uint32_t)q.shift16 | ((uint32_t)q.scale16 << 16);
+    }
+    __syncthreads();
+
+    // C: codes of the lane's blocks, OR-ed into the record image
+#pragma unroll
+    for (int ct = 0; ct < NTW; ++ct) {
+        const uint32_t info = P->blk[2 * (wc * NTW + ct) + h];
+        const uint32_t bits = info & 0xffu;
+        if (bits != 0u) {
+            const uint32_t g = (info >> 8) & 0xffu;
+            const uint32_t pos0 = (info >> 16) * 16u;
+            const float qmax = (float)((1u << bits) - 1u);
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const int tw = wt * 64 + tt * 32 + l32;
+                const float2 sq = gq[g * TOK_WG + tw];
+                uint32_t* row = rec + tw * rstride;
+                const f32x16& d = acc[tt][ct];
+                uint32_t c[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float q = __fmul_rn(__fsub_rn(d[i], sq.x), sq.y);
+                    q = __builtin_amdgcn_fmed3f(__builtin_rintf(q), 0.0f, qmax);
+                    c[i] = (uint32_t)q;
+                }
+                if (bits <= 8u) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const uint32_t v = c[4 * k] | (c[4 * k + 1] << bits) | (c[4 * k + 2] << (2u * bits)) |
+                                           (c[4 * k + 3] << (3u * bits));
+                        put_bits(row, pos0 + 4u * k * bits, v, 4u * bits);
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const uint32_t v = c[2 * k] | (c[2 * k + 1] << bits);
+                        put_bits(row, pos0 + 2u * k * bits, v, 2u * bits);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    __syncthreads();
+
+    // D: the tile's records are contiguous in the stream: one coalesced copy
+    {
+        const int n_valid = min(TOK_WG, T - tok_tile0);
+        uint32_t* out = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.stream_buf) + tr.offset) +
+                        (size_t)tok_tile0 * rd;
+        const uint32_t magic = 0xffffffffu / (uint32_t)rd + 1u;     // exact floor(i / rd) for i < 2^20
+        const int total = n_valid * rd;
+        for (int i = tid; i < total; i += kThreads) {
+            const uint32_t t = __umulhi((uint32_t)i, magic);
+            out[i] = rec[t * rstride + ((uint32_t)i - t * rd)];
+        }
+    }
+    __syncthreads();
+}
+
+template <typename XT>
+__global__ void __launch_bounds__(kThreads) kvtc_encode_kernel(const KernelArgs a) {
+    extern __shared__ uint4 smem[];
+    uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
+    uint4* work = smem + kJobTableBytes / 16 + 1;
+    const uint32_t total = build_tile_table<true>(a, tile_start, reinterpret_cast<uint32_t*>(work));
+    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
+        const TileRef tr = find_tile(a, tile_start, tile);
+        const PlanDev* P = a.plans + tr.plan;
+        const int key = __builtin_amdgcn_readfirstlane(P->enc_wc * 100 + P->enc_ntw);
+        switch (key) {
+#define KVTC_CASE(WC, NTW) case (WC) * 100 + (NTW): encode_tile<NTW, WC, XT>(P, tr, a, work); break;
+            KVTC_CASE(1, 2) KVTC_CASE(1, 4) KVTC_CASE(1, 6) KVTC_CASE(1, 8) KVTC_CASE(1, 10)
+            KVTC_CASE(2, 6) KVTC_CASE(2, 8) KVTC_CASE(2, 10)
+            KVTC_CASE(4, 6) KVTC_CASE(4, 8)
+#undef KVTC_CASE
+            default: break;
+        }
+    }
+}
+
+hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int grid, size_t lds_bytes, hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kvtc_encode_kernel<uint16_t>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kvtc_encode_kernel<float>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (dtype == KVTC_BF16)
+        hipLaunchKernelGGL(kvtc_encode_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+    else
+        hipLaunchKernelGGL(kvtc_encode_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace kvtc

@@ -1,0 +1,327 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on identical inputs.
+
+Bars (written out here):
+  * packed stream: the GPU stream must equal the oracle's packing of the GPU's own headers
+    and codes bit for bit (canonical layout, zero padding);
+  * codes: differ from the oracle's by at most 1 LSB on at most 1e-4 of the entries
+    (rounding-boundary ties follow the fp32 projection, whose summation order differs);
+    headers may differ by one fp16 ulp on a small fraction of (token, group) pairs for the
+    same reason -- reported, bounded at 1 %;
+  * reconstruction: within 1e-2 of the tensor's range (max - min) of the oracle's float64
+    decode of the same stream, and within bf16-output rounding of the oracle's decode that
+    feeds bf16 operands like the matrix cores do.
+"""
+import numpy as np
+import pytest
+import torch
+
+import kvtc_oracle as ko
+import kvtc_synth as ks
+import paper_2511_01815_amd as kv
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _gpu_plan(oplan):
+    groups = list(zip(oplan.group_n.tolist(), oplan.group_bits.tolist()))
+    plan = kv.Plan(oplan.p, oplan.r, oplan.mu32, oplan.v_bits, groups)
+    assert plan.record_bytes == oplan.record_bytes
+    return plan
+
+
+def _to_dev(x_host, dtype):
+    """x_host: float32 values (already representable in the cache dtype)."""
+    if dtype == kv.KVTC_BF16:
+        bits = ks.f32_to_bf16_bits(x_host)
+        return torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(x_host, dtype=np.float32)).to(DEV)
+
+
+def _from_dev(t):
+    if t.dtype == torch.bfloat16:
+        return ks.bf16_bits_to_f32(t.view(torch.int16).cpu().numpy().view(np.uint16))
+    return t.cpu().numpy()
+
+
+def _ulp_apart(a16, b16):
+    """|difference| in fp16 ulps between two fp16 bit-pattern arrays (as ordered integers)."""
+    def key(u):
+        u = u.astype(np.int32)
+        return np.where(u & 0x8000, -(u & 0x7fff), u & 0x7fff)
+    return np.abs(key(a16) - key(b16))
+
+
+def check_stream(oplan, x_vals, rec_gpu, label=""):
+    """Codes / headers / packing of a GPU stream against the oracle.  x_vals: the bf16-exact
+    input values the kernel saw.  Returns stats."""
+    T = x_vals.shape[0]
+    assert rec_gpu.shape == (T, oplan.record_bytes)
+    d32 = ko.project(oplan, x_vals)
+    sh_r, sc_r, co_r = ko.quantise(oplan, d32)
+    sh_g, sc_g, co_g = ko.unpack(oplan, rec_gpu)
+    # bit-exact packing of identical codes
+    np.testing.assert_array_equal(ko.pack(oplan, sh_g, sc_g, co_g), rec_gpu, err_msg=f"{label}: stream not canonical")
+    # headers
+    sh_ne = sh_g.view(np.uint16) != sh_r.view(np.uint16)
+    sc_ne = sc_g.view(np.uint16) != sc_r.view(np.uint16)
+    hdr_rate = float((sh_ne | sc_ne).mean())
+    assert _ulp_apart(sh_g.view(np.uint16), sh_r.view(np.uint16)).max() <= 1, label
+    assert _ulp_apart(sc_g.view(np.uint16), sc_r.view(np.uint16)).max() <= 1, label
+    assert hdr_rate <= 1e-2, (label, hdr_rate)
+    # codes
+    diff = np.abs(co_g.astype(np.int64) - co_r.astype(np.int64))
+    rate = float((diff != 0).mean())
+    assert diff.max() <= 1, (label, int(diff.max()))
+    # 1e-4 is the bar for the widths calibration produces (<= 8 bits).  A code flips when the
+    # fp32 projection error (relative ~2^-22 of the group range after 64 accumulation steps)
+    # straddles a rounding boundary, i.e. with probability ~2^b * 2^-21 per entry; plans built
+    # by hand with wider codes get that arithmetic bound instead.
+    bar = 1e-4 if oplan.coef_bits.max() <= 8 else max(1e-4, float(np.mean(2.0 ** oplan.coef_bits)) * 2.0 ** -20)
+    if rate > bar:
+        # a header that moved by one ulp shifts every code boundary of its group; compare
+        # those groups against the oracle's decision taken with the GPU's header
+        bad_g = (sh_ne | sc_ne)[:, oplan.coef_group]
+        sh32 = sh_g.astype(np.float32)[:, oplan.coef_group]
+        sc32 = sc_g.astype(np.float32)[:, oplan.coef_group]
+        with np.errstate(divide="ignore"):
+            inv = np.where(sc32 > 0, np.float32(1) / sc32, np.float32(0)).astype(np.float32)
+        qmax = ((1 << oplan.coef_bits) - 1).astype(np.float32)[None, :]
+        alt = np.clip(np.rint((d32 - sh32) * inv), 0, qmax).astype(np.int64)
+        diff2 = np.where(bad_g, np.abs(co_g.astype(np.int64) - alt), diff)
+        rate2 = float((diff2 != 0).mean())
+        assert diff2.max() <= 1 and rate2 <= bar, (label, rate, rate2)
+        rate = rate2
+    return dict(code_rate=rate, hdr_rate=hdr_rate)
+
+
+def check_recon(oplan, rec_gpu, xh_gpu, x_vals, out_bf16, label=""):
+    rng_x = float(x_vals.max() - x_vals.min())
+    ref = ko.decode(oplan, rec_gpu)                         # definition, float64
+    err = np.abs(xh_gpu.astype(np.float64) - ref).max()
+    assert err <= 1e-2 * rng_x, (label, err, rng_x)
+    mirror = ko.decode(oplan, rec_gpu, operand_bf16=True)   # bf16 operands, exact sums
+    tol = 3e-5 * np.abs(mirror).max() + (2.0 ** -8 * np.abs(mirror) if out_bf16 else 0.0)
+    assert np.all(np.abs(xh_gpu.astype(np.float64) - mirror) <= tol), (label, np.abs(xh_gpu - mirror).max())
+    return err / rng_x
+
+
+def roundtrip(oplan, plan, x_vals, dtype, ld_pad=0, label=""):
+    T, p = x_vals.shape
+    ld = p + ld_pad
+    xd = torch.zeros((T, ld), dtype=torch.bfloat16 if dtype == kv.KVTC_BF16 else torch.float32, device=DEV)
+    xd[:, :p] = _to_dev(x_vals, dtype)
+    R = plan.record_bytes
+    guard = 64
+    out = torch.full((T * R + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    kv.kvtc_encode(plan.handle, xd, dtype, T, ld, out, T * R)
+    xh = torch.full_like(xd, 7.0)
+    kv.kvtc_decode(plan.handle, out, T * R, T, xh, dtype, ld)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    assert np.all(o[T * R:] == 0xA5), f"{label}: wrote past the stream"
+    rec = o[:T * R].reshape(T, R)
+    if ld_pad:
+        assert torch.all(xh[:, p:] == 7.0), f"{label}: wrote into the row padding"
+    xh_host = _from_dev(xh[:, :p].contiguous())
+    seen = ko.bf16_round(x_vals)
+    st = check_stream(oplan, seen, rec, label)
+    st["recon"] = check_recon(oplan, rec, xh_host, seen, dtype == kv.KVTC_BF16, label)
+    return st
+
+
+# ---- fixtures: calibrated plans ---------------------------------------------------------------------
+
+@pytest.fixture(scope="module")
+def c1():
+    wl = ks.WORKLOADS["c1"]
+    L = ks.make_layer(ks.layer_spec("c1", 0, 0))
+    C_ = ko.bf16_round(ks.draw_f32(L, wl.n_calib, ks.CALIB_DRAW))
+    oplan, _ = ko.calibrate(C_, 4.0)
+    return L, oplan, _gpu_plan(oplan)
+
+
+@pytest.fixture(scope="module")
+def c2():
+    wl = ks.WORKLOADS["c2"]
+    out = {}
+    for kvi in (0, 1):
+        L = ks.make_layer(ks.layer_spec("c2", 0, kvi))
+        C_ = ks.bf16_bits_to_f32(ks.draw_bf16(L, wl.n_calib, ks.CALIB_DRAW))
+        mu, V, S = ko.pca(C_)
+        errs = ko.dp_errors(C_, mu, V)
+        plans = {cr: ko.calibrate_from_pca(C_, mu, V, S, cr, errors=errs)[0] for cr in ((8.0, 16.0, 40.0) if kvi == 0 else (16.0,))}
+        out[kvi] = (L, plans)
+    return out
+
+
+# ---- tests ------------------------------------------------------------------------------------------
+
+def test_config1_fp32_whole_tensor(c1):
+    L, oplan, plan = c1
+    X = ks.draw_f32(L, ks.WORKLOADS["c1"].n_tokens, ks.TEST_DRAW)
+    st = roundtrip(oplan, plan, X, kv.KVTC_F32, label="c1")
+    print("c1", st)
+
+
+@pytest.mark.parametrize("T", [1, 31, 33, 255, 257, 1000])
+def test_ragged_tails(c1, T):
+    L, oplan, plan = c1
+    X = ks.draw_f32(L, T, 77 + T)
+    roundtrip(oplan, plan, X, kv.KVTC_F32, label=f"tail{T}")
+    roundtrip(oplan, plan, ko.bf16_round(X), kv.KVTC_BF16, ld_pad=24, label=f"tail{T}-bf16-strided")
+
+
+def test_config2_single_layer_16x(c2):
+    wl = ks.WORKLOADS["c2"]
+    for kvi, T in ((0, wl.n_tokens), (1, 5000)):
+        L, plans = c2[kvi]
+        oplan = plans[16.0]
+        plan = _gpu_plan(oplan)
+        X = ks.bf16_bits_to_f32(ks.draw_bf16(L, T, ks.TEST_DRAW))
+        st = roundtrip(oplan, plan, X, kv.KVTC_BF16, label=f"c2-kv{kvi}")
+        print("c2", kvi, "r", oplan.r, "R", oplan.record_bytes, st)
+        assert oplan.record_bytes <= 128
+
+
+@pytest.mark.parametrize("cr", [8.0, 40.0])
+def test_config2_other_ratios(c2, cr):
+    L, plans = c2[0]
+    oplan = plans[cr]
+    plan = _gpu_plan(oplan)
+    X = ks.bf16_bits_to_f32(ks.draw_bf16(L, 4099, ks.TEST_DRAW + 1))
+    st = roundtrip(oplan, plan, X, kv.KVTC_BF16, label=f"c2@{cr}")
+    print("c2", cr, "r", oplan.r, st)
+
+
+def _manual(p, groups, seed):
+    rng = np.random.default_rng(seed)
+    V = np.linalg.qr(rng.standard_normal((p, p)))[0]
+    mu = rng.standard_normal(p) * 0.1
+    blocks, s = [], 0
+    for n, b in groups:
+        blocks.append(ko.Block(s, n, b))
+        s += n
+    return ko.compile_plan(mu, V, blocks)
+
+
+@pytest.mark.parametrize("name,p,groups", [
+    ("all-widths", 128, [(16, 16), (16, 12), (16, 9), (16, 7), (16, 5), (16, 3), (16, 2), (16, 1)]),
+    ("full-rank-1024", 1024, [(16, 8), (16, 6), (64, 5), (64, 4), (96, 3), (256, 2), (512, 1)]),
+    ("one-wide-group", 1024, [(1024, 2)]),
+    ("mid-rank-640", 1024, [(64, 7), (256, 3), (320, 2)]),
+    ("gap-in-middle", 256, [(16, 6), (0, 0), (32, 3)]),
+    ("tiny", 64, [(16, 4)]),
+])
+def test_manual_plans(name, p, groups):
+    if name == "gap-in-middle":          # a zero-width block between kept groups
+        rng = np.random.default_rng(5)
+        V = np.linalg.qr(rng.standard_normal((p, p)))[0]
+        oplan = ko.compile_plan(rng.standard_normal(p) * 0.1, V,
+                                [ko.Block(0, 16, 6), ko.Block(16, 48, 0), ko.Block(64, 32, 3), ko.Block(96, 160, 0)])
+        assert oplan.r == 48
+    else:
+        oplan = _manual(p, groups, 11)
+    plan = _gpu_plan(oplan)
+    rng = np.random.default_rng(21)
+    scale = np.arange(1, p + 1, dtype=np.float64) ** -0.7
+    X = ko.bf16_round(((rng.standard_normal((777, p)) * scale) @ np.linalg.qr(rng.standard_normal((p, p)))[0]
+                       + 0.05).astype(np.float32))
+    st = roundtrip(oplan, plan, X, kv.KVTC_BF16, label=name)
+    st2 = roundtrip(oplan, plan, X, kv.KVTC_F32, label=name + "-f32")
+    print(name, st, st2)
+
+
+def test_degenerate_inputs(c1):
+    L, oplan, plan = c1
+    p = oplan.p
+    X = np.zeros((300, p), dtype=np.float32)                 # constant tokens: zero range in every group
+    X[100:200] = oplan.mu32[None, :]
+    X[200:] = 3.0
+    roundtrip(oplan, plan, ko.bf16_round(X), kv.KVTC_BF16, label="constant")
+    # n_tokens == 0 is a no-op; capacity errors come back as status codes
+    buf = torch.zeros(64, dtype=torch.uint8, device=DEV)
+    x = torch.zeros((4, p), dtype=torch.bfloat16, device=DEV)
+    kv.kvtc_encode(plan.handle, x, kv.KVTC_BF16, 0, p, buf, 0)
+    with pytest.raises(kv.KvtcError) as e:
+        kv.kvtc_encode(plan.handle, x, kv.KVTC_BF16, 4, p, buf, 4 * plan.record_bytes - 1)
+    assert e.value.status == 3
+    with pytest.raises(kv.KvtcError) as e:
+        kv.kvtc_decode(plan.handle, buf, 10, 4, x, kv.KVTC_BF16, p)
+    assert e.value.status == 3
+    with pytest.raises(kv.KvtcError) as e:
+        kv.kvtc_encode(plan.handle, x, kv.KVTC_BF16, 4, p - 8, buf, 1 << 20)
+    assert e.value.status == 1
+    with pytest.raises(kv.KvtcError) as e:
+        kv.kvtc_encode(plan.handle, x.view(torch.uint8).flatten()[2:].data_ptr(), kv.KVTC_BF16, 1, p, buf, 1 << 20)
+    assert e.value.status == 1
+    torch.cuda.synchronize()
+
+
+def test_batched_ragged_jobs_with_gpu_offsets(c1, c2):
+    """Several tensors, different plans and lengths, one launch per direction; offsets from the GPU
+    prefix sum equal the host cumulative sum; an over-capacity job is skipped and reported."""
+    _, plans2 = c2[0]
+    oplans = [plans2[16.0], plans2[40.0], plans2[8.0]]
+    gplans = [_gpu_plan(o) for o in oplans]
+    batch = kv.Batch(gplans)
+    L = c2[0][0]
+    lens = [700, 0, 1, 513, 2049, 300]
+    pidx = [0, 1, 2, 1, 0, 2]
+    row0 = np.concatenate([[0], np.cumsum(lens)[:-1]]) + 3          # rows start at 3: base offset honoured
+    total_rows = int(sum(lens)) + 3
+    Xall = ks.bf16_bits_to_f32(ks.draw_bf16(L, total_rows, 4242))
+    xd = _to_dev(Xall, kv.KVTC_BF16)
+    jobs = kv.make_jobs(pidx, lens, row0)
+    jobs_dev = torch.from_numpy(jobs.view(np.uint8)).to(DEV)
+    offs = torch.zeros(len(lens) + 1, dtype=torch.int64, device=DEV)
+    kv.kvtc_offsets(batch.handle, jobs_dev, len(lens), offs)
+    want = np.concatenate([[0], np.cumsum([n * oplans[i].record_bytes for n, i in zip(lens, pidx)])])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(offs.cpu().numpy(), want)
+    cap = int(want[-1])
+    out = torch.full((cap + 64,), 0x5A, dtype=torch.uint8, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    kv.kvtc_encode_batch(batch.handle, jobs_dev, len(lens), xd, kv.KVTC_BF16, 1024, offs, out, cap, status)
+    xh = torch.zeros_like(xd)
+    status2 = torch.zeros(1, dtype=torch.int32, device=DEV)
+    kv.kvtc_decode_batch(batch.handle, jobs_dev, len(lens), out, cap, offs, xh, kv.KVTC_BF16, 1024, status2)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0 and int(status2.item()) == 0
+    o = out.cpu().numpy()
+    assert np.all(o[cap:] == 0x5A)
+    xh_host = _from_dev(xh)
+    assert np.all(xh_host[:3] == 0)
+    for j, (n, i) in enumerate(zip(lens, pidx)):
+        if n == 0:
+            continue
+        rec = o[want[j]:want[j + 1]].reshape(n, -1)
+        xv = Xall[row0[j]:row0[j] + n]
+        check_stream(oplans[i], xv, rec, f"job{j}")
+        check_recon(oplans[i], rec, xh_host[row0[j]:row0[j] + n], xv, True, f"job{j}")
+        # the batched stream equals what the single-tensor entry point writes
+        single = torch.zeros(n * oplans[i].record_bytes, dtype=torch.uint8, device=DEV)
+        kv.kvtc_encode(gplans[i].handle, xd[row0[j]:], kv.KVTC_BF16, n, 1024, single, single.numel())
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(single.cpu().numpy().reshape(n, -1), rec)
+    # capacity: cut the buffer inside job 4 -> jobs 4 and 5 are skipped, status = 1 + 4
+    out2 = torch.full((cap + 64,), 0x5A, dtype=torch.uint8, device=DEV)
+    status.zero_()
+    small = int(want[4]) + 100
+    kv.kvtc_encode_batch(batch.handle, jobs_dev, len(lens), xd, kv.KVTC_BF16, 1024, offs, out2, small, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 5
+    o2 = out2.cpu().numpy()
+    np.testing.assert_array_equal(o2[:want[4]], o[:want[4]])
+    assert np.all(o2[want[4]:] == 0x5A)
+    # a bad plan index is reported the same way
+    jobs_bad = kv.make_jobs([0, 9], [10, 10], [0, 10])
+    jb = torch.from_numpy(jobs_bad.view(np.uint8)).to(DEV)
+    offs2 = torch.zeros(3, dtype=torch.int64, device=DEV)
+    kv.kvtc_offsets(batch.handle, jb, 2, offs2)
+    status.zero_()
+    kv.kvtc_encode_batch(batch.handle, jb, 2, xd, kv.KVTC_BF16, 1024, offs2, out2, cap, status)
+    torch.cuda.synchronize()
+    assert offs2.cpu().numpy().tolist() == [0, 10 * oplans[0].record_bytes, 10 * oplans[0].record_bytes]
+    assert int(status.item()) == 2

@@ -1,0 +1,105 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, rejects bad
+arguments before touching the GPU, and its scalar quantiser numerics (compiled from the same
+header the kernels use) agree bit for bit with the oracle's."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import kvtc_oracle as ko
+import paper_2511_01815_amd as kv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "kvtc.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = sorted(set(re.findall(r"\b(kvtc_[a-z0-9_]+)\s*\(", hdr)))
+    assert {"kvtc_plan_create", "kvtc_encode", "kvtc_decode", "kvtc_offsets", "kvtc_encode_batch",
+            "kvtc_decode_batch", "kvtc_batch_create", "kvtc_last_error"} <= set(names)
+    L = kv.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def _probe():
+    rng = np.random.default_rng(2)
+    tab = np.arange(65536, dtype=np.uint32).astype(np.uint16).view(np.float16)
+    tab = tab[np.isfinite(tab)].astype(np.float32)
+    xs = [rng.standard_normal(3000) * s for s in (1e-9, 1e-7, 3e-5, 1e-2, 1.0, 500.0, 8e4)]
+    xs += [tab[::7], np.nextafter(tab[::11], np.float32(np.inf)), np.nextafter(tab[::13], np.float32(-np.inf))]
+    xs.append(np.array([0.0, -0.0, 65504.0, -65504.0, 65519.9, 1e30, -1e30, np.inf, -np.inf, 5.9e-8, -2.9e-8, 2.98e-8]))
+    return np.concatenate(xs).astype(np.float32)
+
+
+def test_directed_fp16_rounding_matches_oracle_bits():
+    L = kv.lib()
+    x = _probe()
+    want_dn = ko.fp16_floor(x).view(np.uint16)
+    want_up = ko.fp16_ceil(x).view(np.uint16)
+    got_dn = np.array([L.kvtc_host_f16_round_down(float(v)) for v in x], dtype=np.uint16)
+    got_up = np.array([L.kvtc_host_f16_round_up(float(v)) for v in x], dtype=np.uint16)
+    np.testing.assert_array_equal(got_dn, want_dn)
+    np.testing.assert_array_equal(got_up, want_up)
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 6, 8, 11, 16])
+def test_header_and_code_decision_match_oracle(bits):
+    L = kv.lib()
+    rng = np.random.default_rng(bits)
+    d = (rng.standard_normal((400, 16)) * rng.choice([1e-6, 1e-3, 0.3, 5.0, 900.0], (400, 1))).astype(np.float32)
+    d[:5] = d[:5, :1]                      # zero-range groups
+    d[5, :] = [70000.0, -70000.0] + [1.0] * 14   # saturating
+    shift, scale, codes = ko.quantise_group(d, bits)
+    sh = C.c_uint16()
+    sc = C.c_uint16()
+    for t in range(d.shape[0]):
+        L.kvtc_host_group_header(float(d[t].min()), float(d[t].max()), bits, C.byref(sh), C.byref(sc))
+        assert sh.value == int(shift.view(np.uint16)[t]) and sc.value == int(scale.view(np.uint16)[t]), t
+        got = [L.kvtc_host_code(float(v), sh.value, sc.value, bits) for v in d[t]]
+        assert got == codes[t].tolist(), t
+
+
+def test_argument_errors_need_no_gpu():
+    L = kv.lib()
+    p, r = 64, 16
+    mu = np.zeros(p, dtype=np.float32)
+    v = np.zeros((p, r), dtype=np.uint16)
+    with pytest.raises(kv.KvtcError) as e:
+        kv.kvtc_plan_create(60, 16, np.zeros(60, np.float32), np.zeros((60, 16), np.uint16), [(16, 4)], stream=0)
+    assert e.value.status == 1 and "multiple of 64" in str(e.value)
+    with pytest.raises(kv.KvtcError) as e:
+        kv.kvtc_plan_create(p, r, mu, v, [(16, 17)], stream=0)
+    assert e.value.status == 1
+    with pytest.raises(kv.KvtcError) as e:
+        kv.kvtc_plan_create(p, r, mu, v, [(16, 0)], stream=0)
+    assert e.value.status == 1
+    with pytest.raises(kv.KvtcError) as e:
+        kv.kvtc_plan_create(p, 32, mu, np.zeros((p, 32), np.uint16), [(16, 4)], stream=0)
+    assert e.value.status == 1 and "sum" in str(e.value)
+    with pytest.raises(kv.KvtcError) as e:          # group of 1: valid format, not served by the kernels
+        kv.kvtc_plan_create(p, 17, mu, np.zeros((p, 17), np.uint16), [(16, 4), (1, 8)], stream=0)
+    assert e.value.status == 2
+    with pytest.raises(kv.KvtcError) as e:          # record too large for on-chip staging
+        kv.kvtc_plan_create(1024, 1024, np.zeros(1024, np.float32), np.zeros((1024, 1024), np.uint16),
+                            [(16, 16)] * 64, stream=0)
+    assert e.value.status == 2
+    # null handles
+    assert L.kvtc_record_bytes(None) == 0 and L.kvtc_encoded_bytes(None, 5) == 0
+    L.kvtc_plan_destroy(None)
+    L.kvtc_batch_destroy(None)
+    assert L.kvtc_encode(None, None, 0, 1, 64, None, 0, None) == 1
+    assert L.kvtc_decode(None, None, 0, 1, None, 0, 64, None) == 1
+    assert "null plan" in kv.kvtc_last_error()
+    out = C.c_void_p()
+    assert L.kvtc_batch_create(C.byref(out), None, 0, None) == 1
+
+
+def test_job_struct_layout():
+    assert kv.JOB_DTYPE.itemsize == 16
+    j = kv.make_jobs([0, 1], [5, 7], [0, 5])
+    assert j.tobytes() == (b"\x00\x00\x00\x00\x05\x00\x00\x00" + (0).to_bytes(8, "little") +
+                           b"\x01\x00\x00\x00\x07\x00\x00\x00" + (5).to_bytes(8, "little"))
