@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Throughput of the KVTC hot path on one MI355X.
+
+A step = one pass of the whole path over one batch: stream offsets (GPU prefix sum),
+fused encode of every tensor (one launch), fused decode of every tensor (one launch).
+Workload (default): the Llama-3.1-8B-shaped layer of the second BASELINE configuration
+(K and V, 32768 tokens x 1024 features bf16, 16x plans from the calibration bundles),
+replicated as 32 independent seeded draws so that one batch is the 4 GiB of a full
+8B-shaped 32k-token cache and cannot sit in the 256 MB Infinity Cache.
+Inputs are synthetic, generated on the GPU and resident in HBM before timing starts.
+
+Prints ONE JSON line; see the design doc for the roofline arithmetic.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+
+
+def load_bundle(name: str):
+    import numpy as np
+    path = os.path.join(ROOT, "paper_2511_01815_amd", "plans", name + ".npz")
+    z = np.load(path)
+    return dict(mu32=z["mu32"], v_bits=z["v_bits"], group_n=z["group_n"], group_bits=z["group_bits"])
+
+
+def cpu_baseline(bundles, x_host_by_kv, p):
+    """The oracle's encode + decode, timed as it stands on this machine's host cores."""
+    import numpy as np
+    sys.path.insert(0, os.path.join(ROOT, "oracle"))
+    import kvtc_oracle as ko
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([int(i.get("num_threads", 1)) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    best_e = best_d = 1e30
+    raw = 0
+    plans = [ko.plan_from_arrays(b["mu32"], b["v_bits"], b["group_n"], b["group_bits"]) for b in bundles]
+    for _ in range(2):
+        te = td = 0.0
+        raw = 0
+        for plan, x in zip(plans, x_host_by_kv):
+            t0 = time.perf_counter()
+            rec = ko.encode(plan, x)
+            t1 = time.perf_counter()
+            ko.decode(plan, rec, out="bf16")
+            t2 = time.perf_counter()
+            te += t1 - t0
+            td += t2 - t1
+            raw += x.shape[0] * p * 2
+        best_e, best_d = min(best_e, te), min(best_d, td)
+    return dict(value=2 * raw / (best_e + best_d) / 1e9, unit="GB/s", cores=threads, kind="oracle",
+                sample=f"K and V of one layer, {x_host_by_kv[0].shape[0]} tokens each ({raw / 2**20:.0f} MiB raw bf16), "
+                       f"encode {raw / best_e / 1e9:.3f} GB/s, decode {raw / best_d / 1e9:.3f} GB/s, best of 2, no DEFLATE",
+                host_cpus=len(os.sched_getaffinity(0)))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--cr", type=int, default=16, choices=[8, 16, 20, 40])
+    ap.add_argument("--layers", type=int, default=32, help="independent draws of the layer per batch")
+    ap.add_argument("--tokens", type=int, default=32768)
+    ap.add_argument("--cpu-tokens", type=int, default=32768, help="tokens per tensor in the CPU-baseline sample")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path shards with no exchange step; "
+              "see DESIGN.md); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import kvtc_synth as ks
+    import paper_2511_01815_amd as kv
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    kv.lib()      # fail loudly if the HIP library is missing: there is no other path
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    p, T, NL = 1024, args.tokens, args.layers
+
+    bundles = [load_bundle(f"c2_K_cr{args.cr}"), load_bundle(f"c2_V_cr{args.cr}")]
+    plans = [kv.Plan(p, b["v_bits"].shape[1], b["mu32"], b["v_bits"],
+                     list(zip(b["group_n"].tolist(), b["group_bits"].tolist()))) for b in bundles]
+    batch = kv.Batch(plans)
+    R = [pl.record_bytes for pl in plans]
+    r = [pl.r for pl in plans]
+
+    # ---- inputs, resident in HBM ----
+    layers = [ks.make_layer(ks.layer_spec("c2", 0, kvi)) for kvi in (0, 1)]
+    n_jobs = 2 * NL
+    x = torch.empty((n_jobs * T, p), dtype=torch.bfloat16, device=dev)
+    for j in range(n_jobs):
+        ks.draw_bf16_torch(layers[j % 2], T, 10 + j // 2, dev, out=x[j * T:(j + 1) * T])
+    jobs = kv.make_jobs([j % 2 for j in range(n_jobs)], [T] * n_jobs, [j * T for j in range(n_jobs)])
+    jobs_dev = torch.from_numpy(jobs.view(np.uint8)).to(dev)
+    offs = torch.zeros(n_jobs + 1, dtype=torch.int64, device=dev)
+    cap = sum(T * R[j % 2] for j in range(n_jobs))
+    stream_buf = torch.empty(cap, dtype=torch.uint8, device=dev)
+    x_hat = torch.empty_like(x)
+    status = torch.zeros(2, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4 * (args.steps + args.warmup))]
+
+    def step(i):
+        e0, e1, e2, e3 = ev[4 * i:4 * i + 4]
+        kv.kvtc_offsets(batch.handle, jobs_dev, n_jobs, offs)
+        e0.record()
+        kv.kvtc_encode_batch(batch.handle, jobs_dev, n_jobs, x, kv.KVTC_BF16, p, offs, stream_buf, cap, status[0:1])
+        e1.record()
+        e2.record()
+        kv.kvtc_decode_batch(batch.handle, jobs_dev, n_jobs, stream_buf, cap, offs, x_hat, kv.KVTC_BF16, p, status[1:2])
+        e3.record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.warmup, args.warmup + args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    assert status.cpu().tolist() == [0, 0], "a job was skipped"
+    assert int(offs[-1].item()) == cap
+
+    enc_ms = [ev[4 * i].elapsed_time(ev[4 * i + 1]) for i in range(args.warmup, args.warmup + args.steps)]
+    dec_ms = [ev[4 * i + 2].elapsed_time(ev[4 * i + 3]) for i in range(args.warmup, args.warmup + args.steps)]
+    enc_avg, dec_avg = sum(enc_ms) / len(enc_ms), sum(dec_ms) / len(dec_ms)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    raw_bytes = n_jobs * T * p * 2
+
+    # sanity of the timed work: reconstruction error of the last step is what 16x should give
+    with torch.no_grad():
+        a = x[:T].float()
+        b = x_hat[:T].float()
+        rel = float((b - a).norm() / (a - a.mean(0)).norm())
+    assert rel < 0.25, rel
+
+    # ---- roofline of the dominant kernel (per launch) ----
+    alg_bytes = sum(T * (2 * p + R[j % 2]) for j in range(n_jobs))
+    flops = sum(T * 2 * p * r[j % 2] for j in range(n_jobs))
+    dom, dom_ms = ("kvtc_encode_kernel", enc_avg) if enc_avg >= dec_avg else ("kvtc_decode_kernel", dec_avg)
+    t_hbm = alg_bytes / (HBM_PEAK_GBPS * 1e9)
+    t_mfma = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_mfma:
+        roof = dict(bound="hbm", achieved=alg_bytes / (dom_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBPS, unit="GB/s")
+    else:
+        roof = dict(bound="mfma", achieved=flops / (dom_ms * 1e-3) / 1e12, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s")
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = dom
+    roof["encode"] = dict(ms=enc_avg, raw_GBps=raw_bytes / enc_avg / 1e6,
+                          hbm_frac=alg_bytes / (enc_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                          mfma_frac=flops / (enc_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
+    roof["decode"] = dict(ms=dec_avg, raw_GBps=raw_bytes / dec_avg / 1e6,
+                          hbm_frac=alg_bytes / (dec_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                          mfma_frac=flops / (dec_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
+
+    result = {
+        "metric": "encode/decode GB/s of bf16 KV at 16x (8B-shaped); % of binding roofline",
+        "value": 2 * raw_bytes / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"c2 layer (K+V, {T} tok x 1024 bf16, {args.cr}x, r={r[0]}/{r[1]}, R={R[0]}/{R[1]} B) "
+                               f"x {NL} seeded draws in one batch = {raw_bytes / 2**30:.2f} GiB raw KV; "
+                               "step = offsets + encode + decode",
+                   "compression": args.cr, "n_jobs": n_jobs},
+        "roofline": roof,
+    }
+    if not args.no_cpu:
+        nt = min(args.cpu_tokens, T)
+        xs = [ks.bf16_bits_to_f32(x[j * T:j * T + nt].view(torch.int16).cpu().numpy().view(np.uint16)) for j in (0, 1)]
+        result["cpu_baseline"] = cpu_baseline(bundles, xs, p)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

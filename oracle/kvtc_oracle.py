@@ -464,3 +464,27 @@ def inflate(blob: bytes, plan: Plan) -> np.ndarray:
 def compression_ratios(plan: Plan, n_tokens: int, records: np.ndarray, level: int = 6):
     raw = 2 * plan.p * n_tokens
     return raw / records.size, raw / len(deflate(records, level))
+
+
+# --------------------------------------------------------------------------
+# plan bundles on disk (the calibration result is data for the coder)
+# --------------------------------------------------------------------------
+
+def plan_from_arrays(mu32: np.ndarray, v_bits: np.ndarray, group_n, group_bits) -> Plan:
+    """Rebuild a Plan from what a bundle stores: mean, kept basis columns (bf16 bits) and
+    the kept groups.  The kept coordinates are renumbered 0..r-1."""
+    p, r = v_bits.shape
+    blocks, s = [], 0
+    for n, b in zip(group_n, group_bits):
+        blocks.append(Block(s, int(n), int(b)))
+        s += int(n)
+    assert s == r
+    plan = compile_plan(np.asarray(mu32, dtype=np.float32), bf16_to_f32(v_bits).astype(np.float64), blocks)
+    assert np.array_equal(plan.v_bits, np.asarray(v_bits, dtype=np.uint16))
+    return plan
+
+
+def save_plan(path: str, plan: Plan, **meta) -> None:
+    np.savez(path, mu32=plan.mu32, v_bits=plan.v_bits, group_n=plan.group_n.astype(np.int32),
+             group_bits=plan.group_bits.astype(np.int32), kept=plan.kept.astype(np.int32),
+             **{k: np.asarray(v) for k, v in meta.items()})
