@@ -119,7 +119,7 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
  * Batched / ragged calls: many tensors (jobs), each with its own plan and length, in
  * one launch per direction.  A kvtc_batch makes the plans' descriptors addressable
  * from the device; it copies what it needs, but the plans must outlive it.
- * At most 2048 jobs per call (KVTC_E_UNSUPPORTED beyond).
+ * At most 1024 jobs per call (KVTC_E_UNSUPPORTED beyond).
  */
 kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, int n_plans,
                               kvtc_stream stream);

@@ -14,8 +14,10 @@
 #include "kvtc_numeric.h"
 
 namespace kvtc {
-hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int grid, size_t lds_bytes, hipStream_t stream);
-hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int grid, size_t lds_bytes, hipStream_t stream);
+hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream);
+hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream);
+int encode_lds_bytes(int ntw, int wc, int n_groups, int rec_dwords, kvtc_dtype dtype);
+int decode_lds_bytes(int nct, int tt, int rec_dwords);
 }  // namespace kvtc
 
 using namespace kvtc;
@@ -30,7 +32,8 @@ struct kvtc_plan {
 struct kvtc_batch {
     PlanDev* plans_dev;
     int n_plans;
-    int enc_lds, dec_lds;   // max over the plans
+    int enc_lds[2], dec_lds[2];   // max over the plans of each kernel flavour (narrow, wide); -1: none
+    int max_p;
     std::vector<int32_t> rec_dwords;
     uint32_t* rec_dwords_dev;
 };
@@ -164,25 +167,27 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     const int nt = (r + 31) / 32;
 
     // encode variant: NTW coordinate tiles per wave, WC waves across coordinates
-    static const int enc_tab[][2] = {{1, 2}, {1, 4}, {1, 6}, {1, 8}, {1, 10}, {2, 6}, {2, 8}, {2, 10}, {4, 6}, {4, 8}};
+    // {waves across coordinates, tiles per wave, wide kernel?}, ascending padded width
+    static const int enc_tab[][3] = {{1, 2, 0}, {1, 4, 0}, {2, 3, 0}, {2, 4, 0}, {2, 5, 0},
+                                     {2, 6, 1}, {2, 8, 1}, {2, 10, 1}, {4, 6, 1}, {4, 8, 1}};
     d.enc_wc = 0;
     for (auto& e : enc_tab)
-        if (e[0] * e[1] >= nt) { d.enc_wc = e[0]; d.enc_ntw = e[1]; break; }
-    static const int dec_tab[][2] = {{2, 2}, {2, 4}, {2, 6}, {2, 8}, {2, 10}, {1, 12}, {1, 16}, {1, 20}, {1, 24}, {1, 32}};
+        if (e[0] * e[1] >= nt) { d.enc_wc = e[0]; d.enc_ntw = e[1]; d.enc_wide = e[2]; break; }
+    // {token tiles per wave, coordinate tiles, wide kernel?}
+    static const int dec_tab[][3] = {{2, 2, 0}, {2, 4, 0}, {2, 6, 0}, {2, 8, 0}, {2, 10, 0},
+                                     {1, 12, 1}, {1, 16, 1}, {1, 20, 1}, {1, 24, 1}, {1, 32, 1}};
     d.dec_tt = 0;
     for (auto& e : dec_tab)
-        if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; break; }
+        if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; d.dec_wide = e[2]; break; }
     if (d.enc_wc == 0 || d.dec_tt == 0) return fail(KVTC_E_UNSUPPORTED, "kvtc_plan_create: no kernel variant for r=%d", r);
     const int ntp = d.enc_ntw * d.enc_wc;
     d.enc_tok_wg = 64 * (4 / d.enc_wc);
     d.dec_tok_wg = 4 * 32 * d.dec_tt;
     {
-        const int main_b = 2 * 2 * ntp * 1024;
-        const int epi_b = d.enc_tok_wg * (2 * ntp * 8 + n_groups * 8 + (d.rec_dwords + 1) * 4);
-        d.enc_lds = main_b > epi_b ? main_b : epi_b;
-        const int rec_b = d.dec_tok_wg * (d.rec_dwords + 1) * 4;
-        const int slab_b = 2 * 2 * d.dec_nct * 1024;
-        d.dec_lds = rec_b > slab_b ? rec_b : slab_b;
+        const int e16 = encode_lds_bytes(d.enc_ntw, d.enc_wc, n_groups, d.rec_dwords, KVTC_BF16);
+        const int e32 = encode_lds_bytes(d.enc_ntw, d.enc_wc, n_groups, d.rec_dwords, KVTC_F32);
+        d.enc_lds = e16 > e32 ? e16 : e32;
+        d.dec_lds = decode_lds_bytes(d.dec_nct, d.dec_tt, d.rec_dwords);
     }
     const int lds_cap = kLdsBudget - kJobTableBytes - 64;
     if (d.enc_lds > lds_cap || d.dec_lds > lds_cap)
@@ -336,8 +341,9 @@ kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dty
     a.cap = out_cap;
     a.status = nullptr;
     const int64_t tiles = (n_tokens + plan->h.enc_tok_wg - 1) / plan->h.enc_tok_wg;
-    const int grid = (int)(tiles < cu_count() ? tiles : cu_count());
-    hipError_t e = launch_encode(a, dtype, grid, (size_t)kJobTableBytes + 64 + plan->h.enc_lds, static_cast<hipStream_t>(stream));
+    const int slots = cu_count() * (plan->h.enc_wide ? 1 : 2);
+    const int grid = (int)(tiles < slots ? tiles : slots);
+    hipError_t e = launch_encode(a, dtype, plan->h.enc_wide, grid, (size_t)kJobTableBytes + 64 + plan->h.enc_lds, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }
@@ -364,8 +370,9 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
     a.stream_buf = const_cast<void*>(in_dev);
     a.cap = in_bytes;
     const int64_t tiles = (n_tokens + plan->h.dec_tok_wg - 1) / plan->h.dec_tok_wg;
-    const int grid = (int)(tiles < cu_count() ? tiles : cu_count());
-    hipError_t e = launch_decode(a, dtype, grid, (size_t)kJobTableBytes + 64 + plan->h.dec_lds, static_cast<hipStream_t>(stream));
+    const int slots = cu_count() * (plan->h.dec_wide ? 1 : 2);
+    const int grid = (int)(tiles < slots ? tiles : slots);
+    hipError_t e = launch_decode(a, dtype, plan->h.dec_wide, grid, (size_t)kJobTableBytes + 64 + plan->h.dec_lds, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }
@@ -379,7 +386,8 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
     b->plans_dev = nullptr;
     b->rec_dwords_dev = nullptr;
     b->n_plans = n_plans;
-    b->enc_lds = b->dec_lds = 0;
+    b->enc_lds[0] = b->enc_lds[1] = b->dec_lds[0] = b->dec_lds[1] = -1;
+    b->max_p = 0;
     for (int i = 0; i < n_plans; ++i) {
         if (!plans[i]) {
             delete b;
@@ -387,8 +395,10 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
         }
         h.push_back(plans[i]->h);
         b->rec_dwords.push_back(plans[i]->h.rec_dwords);
-        if (plans[i]->h.enc_lds > b->enc_lds) b->enc_lds = plans[i]->h.enc_lds;
-        if (plans[i]->h.dec_lds > b->dec_lds) b->dec_lds = plans[i]->h.dec_lds;
+        const PlanDev& ph = plans[i]->h;
+        if (ph.enc_lds > b->enc_lds[ph.enc_wide]) b->enc_lds[ph.enc_wide] = ph.enc_lds;
+        if (ph.dec_lds > b->dec_lds[ph.dec_wide]) b->dec_lds[ph.dec_wide] = ph.dec_lds;
+        if (ph.p > b->max_p) b->max_p = ph.p;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&b->plans_dev), sizeof(PlanDev) * n_plans);
@@ -463,8 +473,13 @@ kvtc_status kvtc_encode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.stream_buf = out_base_dev;
     a.cap = out_cap;
     a.status = status_dev;
-    hipError_t e = launch_encode(a, dtype, cu_count(), (size_t)kJobTableBytes + 64 + batch->enc_lds, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode_batch: launch failed: %s", hipGetErrorString(e));
+    if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_encode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
+    for (int wide = 0; wide < 2; ++wide) {
+        if (batch->enc_lds[wide] < 0) continue;      // no plan of this flavour
+        hipError_t e = launch_encode(a, dtype, wide, cu_count() * (wide ? 1 : 2),
+                                     (size_t)kJobTableBytes + 64 + batch->enc_lds[wide], static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode_batch: launch failed: %s", hipGetErrorString(e));
+    }
     return KVTC_OK;
 }
 
@@ -487,8 +502,13 @@ kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.stream_buf = const_cast<void*>(in_base_dev);
     a.cap = in_bytes;
     a.status = status_dev;
-    hipError_t e = launch_decode(a, dtype, cu_count(), (size_t)kJobTableBytes + 64 + batch->dec_lds, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode_batch: launch failed: %s", hipGetErrorString(e));
+    if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_decode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
+    for (int wide = 0; wide < 2; ++wide) {
+        if (batch->dec_lds[wide] < 0) continue;
+        hipError_t e = launch_decode(a, dtype, wide, cu_count() * (wide ? 1 : 2),
+                                     (size_t)kJobTableBytes + 64 + batch->dec_lds[wide], static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode_batch: launch failed: %s", hipGetErrorString(e));
+    }
     return KVTC_OK;
 }
 

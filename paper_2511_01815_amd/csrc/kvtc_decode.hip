@@ -6,8 +6,8 @@
 // K = kept coordinates.  A lane owns one token; its dequantised coordinates ARE its B operand
 // (16 consecutive coordinates = one block of the record = two k-step fragments), so they are
 // built once per tile and stay in registers while the wave sweeps the feature tiles.
-// V_kept is pre-swizzled into A fragments per 32-feature tile, staged through LDS
-// (double-buffered) and shared by the four wavefronts.  Rows of the A operand are permuted
+// V_kept is pre-swizzled into A fragments per 32-feature tile, moved global -> LDS without
+// register staging (double-buffered) and shared by the four wavefronts.  Rows of the A operand are permuted
 // so that a lane ends up with 16 consecutive features of its token: 32 contiguous bytes of
 // bf16 output per store pair.
 #include <hip/hip_runtime.h>
@@ -29,20 +29,26 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
-template <typename OT> struct OutStore;
-template <> struct OutStore<uint16_t> {
-    static __device__ __forceinline__ void store(uint16_t* p, const f32x16& v) {
-        uint4 a, b;
+// Output registers of one (token tile, feature tile): converted before the workgroup barrier,
+// stored after it, so the stores have a whole step to drain before the next full wait.
+template <typename OT> struct OutRegs;
+template <> struct OutRegs<uint16_t> {
+    uint4 a, b;
+    __device__ __forceinline__ void set(const f32x16& v) {
         a.x = pack_bf16x2(v[0], v[1]);   a.y = pack_bf16x2(v[2], v[3]);
         a.z = pack_bf16x2(v[4], v[5]);   a.w = pack_bf16x2(v[6], v[7]);
         b.x = pack_bf16x2(v[8], v[9]);   b.y = pack_bf16x2(v[10], v[11]);
         b.z = pack_bf16x2(v[12], v[13]); b.w = pack_bf16x2(v[14], v[15]);
+    }
+    __device__ __forceinline__ void store(uint16_t* p) const {
         reinterpret_cast<uint4*>(p)[0] = a;
         reinterpret_cast<uint4*>(p)[1] = b;
     }
 };
-template <> struct OutStore<float> {
-    static __device__ __forceinline__ void store(float* p, const f32x16& v) {
+template <> struct OutRegs<float> {
+    f32x16 v;
+    __device__ __forceinline__ void set(const f32x16& x) { v = x; }
+    __device__ __forceinline__ void store(float* p) const {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             reinterpret_cast<float4*>(p)[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
@@ -55,7 +61,6 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
     constexpr int TOK_W = 32 * TT;
     constexpr int TOK_WG = 4 * TOK_W;
     constexpr int SLAB_U4 = 2 * NCT * 64;          // one 32-feature tile of V_kept
-    constexpr int NST = (SLAB_U4 + kThreads - 1) / kThreads;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
@@ -143,18 +148,7 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
     uint4* slab1 = smem + SLAB_U4;
     const uint4* vg = P->v_dec;
     const int n_ft = p / 32;
-    uint4 stage[NST];
-#pragma unroll
-    for (int i = 0; i < NST; ++i) {
-        const int idx = tid + i * kThreads;
-        if (idx < SLAB_U4) stage[i] = vg[idx];
-    }
-#pragma unroll
-    for (int i = 0; i < NST; ++i) {
-        const int idx = tid + i * kThreads;
-        if (idx < SLAB_U4) slab0[idx] = stage[i];
-    }
-    __syncthreads();
+    dma_slab<SLAB_U4>(vg, slab0, wave, lane);
 
     OT* orow[TT];
     bool valid[TT];
@@ -165,19 +159,13 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
         orow[tt] = reinterpret_cast<OT*>(const_cast<void*>(a.x)) + (tr.x_row0 + (valid[tt] ? t : 0)) * a.ld_x + 16 * h;
     }
     const float* mu = P->mu + 16 * h;
+    wait_vmem_all();
+    __syncthreads();
 
     for (int ft = 0; ft < n_ft; ++ft) {
         const uint4* cur = (ft & 1) ? slab1 : slab0;
         uint4* nxt = (ft & 1) ? slab0 : slab1;
         const bool more = ft + 1 < n_ft;
-        if (more) {
-            const uint4* src = vg + (size_t)(ft + 1) * SLAB_U4;
-#pragma unroll
-            for (int i = 0; i < NST; ++i) {
-                const int idx = tid + i * kThreads;
-                if (idx < SLAB_U4) stage[i] = src[idx];
-            }
-        }
         f32x16 acc[TT];
         {
             f32x16 m;
@@ -189,33 +177,46 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) acc[tt] = m;
         }
+        constexpr int NSTEP = 2 * NCT;
+        const uint4* abase = cur + lane;
+        uint4 af[3];
+        af[0] = abase[0];
+        af[1] = abase[64];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ks = 0; ks < 2 * NCT; ++ks) {
-            const bf16x8 av = as_bf16x8_d(cur[ks * 64 + lane]);
+        for (int ks = 0; ks < NSTEP; ++ks) {
+            if (ks + 2 < NSTEP) af[(ks + 2) % 3] = abase[(ks + 2) * 64];
+            if (ks + 2 == NSTEP - 1) {          // last LDS read of this tile is out: start the next slab
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) dma_slab<SLAB_U4>(vg + (size_t)(ft + 1) * SLAB_U4, nxt, wave, lane);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const bf16x8 av = as_bf16x8_d(af[ks % 3]);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
                 acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bop[tt][ks], acc[tt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        OutRegs<OT> o[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) o[tt].set(acc[tt]);
+        wait_vmem_all();
+        __syncthreads();
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
-            if (valid[tt]) OutStore<OT>::store(orow[tt] + ft * 32, acc[tt]);
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < NST; ++i) {
-                const int idx = tid + i * kThreads;
-                if (idx < SLAB_U4) nxt[idx] = stage[i];
-            }
-        }
-        __syncthreads();
+            if (valid[tt]) o[tt].store(orow[tt] + ft * 32);
     }
+    __syncthreads();
 }
 
+// Two kernels, as for encode: narrow plans (two token tiles per wave, up to 320 padded
+// coordinates) run two workgroups per compute unit, wide ones get the whole register file.
 template <typename OT>
-__global__ void __launch_bounds__(kThreads) kvtc_decode_kernel(const KernelArgs a) {
+__global__ void __launch_bounds__(kThreads, 2) kvtc_decode_kernel(const KernelArgs a) {
     extern __shared__ uint4 smem[];
     uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
     uint4* work = smem + kJobTableBytes / 16 + 1;
-    const uint32_t total = build_tile_table<false>(a, tile_start, reinterpret_cast<uint32_t*>(work));
+    const uint32_t total = build_tile_table<false, 0>(a, tile_start, reinterpret_cast<uint32_t*>(work));
     for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
         const TileRef tr = find_tile(a, tile_start, tile);
         const PlanDev* P = a.plans + tr.plan;
@@ -223,6 +224,24 @@ __global__ void __launch_bounds__(kThreads) kvtc_decode_kernel(const KernelArgs 
         switch (key) {
 #define KVTC_CASE(TT, NCT) case (TT) * 100 + (NCT): decode_tile<NCT, TT, OT>(P, tr, a, work); break;
             KVTC_CASE(2, 2) KVTC_CASE(2, 4) KVTC_CASE(2, 6) KVTC_CASE(2, 8) KVTC_CASE(2, 10)
+#undef KVTC_CASE
+            default: break;
+        }
+    }
+}
+
+template <typename OT>
+__global__ void __launch_bounds__(kThreads, 1) kvtc_decode_wide_kernel(const KernelArgs a) {
+    extern __shared__ uint4 smem[];
+    uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
+    uint4* work = smem + kJobTableBytes / 16 + 1;
+    const uint32_t total = build_tile_table<false, 1>(a, tile_start, reinterpret_cast<uint32_t*>(work));
+    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
+        const TileRef tr = find_tile(a, tile_start, tile);
+        const PlanDev* P = a.plans + tr.plan;
+        const int key = __builtin_amdgcn_readfirstlane(P->dec_tt * 100 + P->dec_nct);
+        switch (key) {
+#define KVTC_CASE(TT, NCT) case (TT) * 100 + (NCT): decode_tile<NCT, TT, OT>(P, tr, a, work); break;
             KVTC_CASE(1, 12) KVTC_CASE(1, 16) KVTC_CASE(1, 20) KVTC_CASE(1, 24) KVTC_CASE(1, 32)
 #undef KVTC_CASE
             default: break;
@@ -230,22 +249,40 @@ __global__ void __launch_bounds__(kThreads) kvtc_decode_kernel(const KernelArgs 
     }
 }
 
-hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int grid, size_t lds_bytes, hipStream_t stream) {
+template <typename K>
+static hipError_t set_lds_attr_d(K kernel) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+}
+
+hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kvtc_decode_kernel<uint16_t>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kvtc_decode_kernel<float>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+        hipError_t e = set_lds_attr_d(&kvtc_decode_kernel<uint16_t>);
+        if (e == hipSuccess) e = set_lds_attr_d(&kvtc_decode_kernel<float>);
+        if (e == hipSuccess) e = set_lds_attr_d(&kvtc_decode_wide_kernel<uint16_t>);
+        if (e == hipSuccess) e = set_lds_attr_d(&kvtc_decode_wide_kernel<float>);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    if (dtype == KVTC_BF16)
-        hipLaunchKernelGGL(kvtc_decode_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
-    else
-        hipLaunchKernelGGL(kvtc_decode_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+    if (!wide) {
+        if (dtype == KVTC_BF16)
+            hipLaunchKernelGGL(kvtc_decode_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+        else
+            hipLaunchKernelGGL(kvtc_decode_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+    } else {
+        if (dtype == KVTC_BF16)
+            hipLaunchKernelGGL(kvtc_decode_wide_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+        else
+            hipLaunchKernelGGL(kvtc_decode_wide_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+    }
     return hipGetLastError();
+}
+
+int decode_lds_bytes(int nct, int tt, int rec_dwords) {
+    const int tok_wg = 4 * 32 * tt;
+    const int rec_b = tok_wg * (rec_dwords + 1) * 4;
+    const int slab_b = 2 * 2 * nct * 1024;
+    return rec_b > slab_b ? rec_b : slab_b;
 }
 
 }  // namespace kvtc

@@ -8,7 +8,7 @@
 namespace kvtc {
 
 constexpr int kThreads = 256;          // 4 wavefronts, one per SIMD of a compute unit
-constexpr int kMaxJobs = 2048;         // jobs per batched launch (tile table lives in LDS)
+constexpr int kMaxJobs = 1024;         // jobs per batched launch (tile table lives in LDS)
 constexpr int kLdsBudget = 160 * 1024; // gfx950 LDS per workgroup
 constexpr int kJobTableBytes = (kMaxJobs + 1) * 4;
 
@@ -21,6 +21,7 @@ struct PlanDev {
     int32_t dec_nct, dec_tt;                // decode variant: coefficient tiles, token tiles per wave
     int32_t enc_tok_wg, dec_tok_wg;         // tokens per workgroup tile
     int32_t enc_lds, dec_lds;               // dynamic LDS bytes needed (without the job table)
+    int32_t enc_wide, dec_wide;             // 0: served by the two-waves-per-SIMD kernel, 1: by the 512-register one
     int32_t pad_;
     const uint4* v_enc;    // [p/16][32*ntp/32][64] MFMA A fragments of V_kept^T (encode)
     const uint4* v_dec;    // [p/32][2*nct][64]     MFMA A fragments of V_kept   (decode)
@@ -54,7 +55,7 @@ struct TileRef {
 // Builds the exclusive prefix of tiles per job in LDS (tile_start[0..n_jobs]) and returns
 // the total.  A job with a bad plan index, a negative token count or a stream that would end
 // beyond `cap` gets zero tiles; workgroup 0 reports the lowest such job in *status.
-template <bool kEncode>
+template <bool kEncode, int kWide>
 __device__ inline uint32_t build_tile_table(const KernelArgs& a, uint32_t* tile_start, uint32_t* scratch /*[kThreads + 1]*/) {
     const int tid = threadIdx.x;
     const int n_jobs = a.jobs ? a.n_jobs : 1;
@@ -72,8 +73,10 @@ __device__ inline uint32_t build_tile_table(const KernelArgs& a, uint32_t* tile_
             bool ok = jb.plan >= 0 && jb.plan < a.n_plans && jb.n_tokens >= 0;
             if (ok && a.offsets) ok = a.offsets[j + 1] <= a.cap && a.offsets[j + 1] >= a.offsets[j];
             if (ok) {
-                const int tw = kEncode ? a.plans[jb.plan].enc_tok_wg : a.plans[jb.plan].dec_tok_wg;
-                tiles = (uint32_t)((jb.n_tokens + tw - 1) / tw);
+                const PlanDev& pl = a.plans[jb.plan];
+                const int tw = kEncode ? pl.enc_tok_wg : pl.dec_tok_wg;
+                // each launch serves the plans of its own kernel flavour; the other launch takes the rest
+                if ((kEncode ? pl.enc_wide : pl.dec_wide) == kWide) tiles = (uint32_t)((jb.n_tokens + tw - 1) / tw);
             } else if (first_bad == 0xffffffffu) {
                 first_bad = (uint32_t)j;
             }
@@ -133,5 +136,23 @@ __device__ inline TileRef find_tile(const KernelArgs& a, const uint32_t* tile_st
     t.tile = __builtin_amdgcn_readfirstlane(t.tile);
     return t;
 }
+
+// 16 bytes per lane from global memory straight into LDS, no register staging: lane i's
+// bytes land at lds_wave_base + 16 * i (lds_wave_base must be wave-uniform).
+__device__ __forceinline__ void dma16(const uint4* gsrc, uint4* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+// Copy n_u4 (a multiple of 256) uint4 from global to LDS with the whole workgroup.
+template <int N_U4>
+__device__ __forceinline__ void dma_slab(const uint4* __restrict__ src, uint4* dst, int wave, int lane) {
+    static_assert(N_U4 % kThreads == 0, "whole rounds of the workgroup");
+#pragma unroll
+    for (int i = 0; i < N_U4 / kThreads; ++i)
+        dma16(src + i * kThreads + wave * 64 + lane, dst + i * kThreads + wave * 64);
+}
+
+__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
 }  // namespace kvtc

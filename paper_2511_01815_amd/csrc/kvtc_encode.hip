@@ -14,7 +14,8 @@
 //   * X is read straight from HBM into the B operand registers (a lane reads 16 contiguous
 //     bytes of its token's row per k-step); every byte of X is read once.
 //   * V_kept is pre-swizzled at plan creation into A-operand fragments; slabs of it are
-//     staged through LDS (double-buffered) and shared by the wavefronts of the workgroup.
+//     moved global -> LDS without register staging (double-buffered) and shared by the
+//     wavefronts of the workgroup.
 //   * For wide plans the coordinates are split over WC wavefronts that share the tokens.
 // Epilogue: block min/max -> LDS -> per (token, group) header (fp16 shift down, scale up)
 // -> codes -> OR-ed into the record image in LDS -> one contiguous, coalesced store of the
@@ -58,6 +59,11 @@ __device__ __forceinline__ void put_bits(uint32_t* rec, uint32_t pos, uint32_t v
     if (s + len > 32u) atomicOr(rec + dw + 1, v >> (32u - s));
 }
 
+// k-steps (16 features each) per LDS slab of the basis
+template <typename XT> __host__ __device__ constexpr int enc_ks(int ntp) {
+    return sizeof(XT) == 2 ? (ntp <= 8 ? 4 : 2) : 2;
+}
+
 template <int NTW, int WC, typename XT>
 __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const TileRef& tr,
                                             const KernelArgs& a, uint4* smem) {
@@ -65,9 +71,8 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
     constexpr int NTP = NTW * WC;            // coordinate tiles of the padded plan
     constexpr int WT = 4 / WC;               // waves across tokens
     constexpr int TOK_WG = 64 * WT;
-    constexpr int KS = 2;                    // k-steps (16 features) per LDS slab
+    constexpr int KS = enc_ks<XT>(NTP);
     constexpr int SLAB_U4 = KS * NTP * 64;
-    constexpr int NST = (SLAB_U4 + kThreads - 1) / kThreads;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wc = wave % WC, wt = wave / WC;
@@ -103,32 +108,26 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
     uint4* slab0 = smem;
     uint4* slab1 = smem + SLAB_U4;
     const uint4* vg = P->v_enc;
-    const int n_slabs = p / (16 * KS);          // even: p is a multiple of 64
-    static_assert(SLAB_U4 % kThreads == 0, "slab copy assumes whole rounds of the workgroup");
+    const int n_slabs = p / (16 * KS);          // p is a multiple of 64 = 16 * max KS
 
-    uint4 stage[NST];
     XFrag<XT> xa[TT][KS], xb[TT][KS];
 
-    // prologue: slab 0 -> LDS, first X batch -> registers
-#pragma unroll
-    for (int i = 0; i < NST; ++i) stage[i] = vg[tid + i * kThreads];
+    // prologue: slab 0 -> LDS (no register staging), first X batch -> registers
+    dma_slab<SLAB_U4>(vg, slab0, wave, lane);
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) xa[tt][ks].load(xrow[tt] + ks * 16);
-#pragma unroll
-    for (int i = 0; i < NST; ++i) slab0[tid + i * kThreads] = stage[i];
+    wait_vmem_all();
     __syncthreads();
 
-    // One slab step: issue the global loads of the next slab and X batch, run the
-    // 2*KS*NTW MFMAs of this slab with the A fragments read from LDS two steps ahead,
-    // then park the next slab in the other LDS buffer.
+    // One slab step.  The X fragments of the next step are requested first (a whole step of
+    // latency cover); the A fragments come from LDS two MFMA groups ahead; the next slab's
+    // global->LDS transfer is issued right after this step's last LDS read, because the
+    // compiler orders every later LDS read behind an outstanding transfer.
     auto slab_step = [&](const uint4* cur, uint4* nxt, XFrag<XT> (&xc)[TT][KS], XFrag<XT> (&xn)[TT][KS], int s) {
         const bool more = s + 1 < n_slabs;
         if (more) {
-            const uint4* src = vg + (size_t)(s + 1) * SLAB_U4;
-#pragma unroll
-            for (int i = 0; i < NST; ++i) stage[i] = src[tid + i * kThreads];
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
@@ -149,21 +148,23 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
         for (int j = 0; j < NSTEP; ++j) {
             const int ks = j / NTW, ct = j % NTW;
             if (j + 2 < NSTEP) af[(j + 2) % 3] = abase[(((j + 2) / NTW) * NTP + ((j + 2) % NTW)) * 64];
+            if (j + 2 == NSTEP - 1) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) dma_slab<SLAB_U4>(vg + (size_t)(s + 1) * SLAB_U4, nxt, wave, lane);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             const bf16x8 av = as_bf16x8(af[j % 3]);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
                 acc[tt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, xv[tt][ks], acc[tt][ct], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < NST; ++i) nxt[tid + i * kThreads] = stage[i];
-        }
+        wait_vmem_all();
         __syncthreads();
     };
     for (int s = 0; s < n_slabs; s += 2) {
         slab_step(slab0, slab1, xa, xb, s);
-        slab_step(slab1, slab0, xb, xa, s + 1);
+        if (s + 1 < n_slabs) slab_step(slab1, slab0, xb, xa, s + 1);
     }
 
     // ---- epilogue -----------------------------------------------------------------
@@ -266,43 +267,85 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
     __syncthreads();
 }
 
+// Two kernels: plans of up to 320 padded coordinates fit in 256 registers per lane and run two
+// workgroups per compute unit (one hides the other's memory waits and epilogue); wider plans
+// get the whole register file.  A batched launch serves only the plans of its own flavour.
 template <typename XT>
-__global__ void __launch_bounds__(kThreads) kvtc_encode_kernel(const KernelArgs a) {
+__global__ void __launch_bounds__(kThreads, 2) kvtc_encode_kernel(const KernelArgs a) {
     extern __shared__ uint4 smem[];
     uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
     uint4* work = smem + kJobTableBytes / 16 + 1;
-    const uint32_t total = build_tile_table<true>(a, tile_start, reinterpret_cast<uint32_t*>(work));
+    const uint32_t total = build_tile_table<true, 0>(a, tile_start, reinterpret_cast<uint32_t*>(work));
     for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
         const TileRef tr = find_tile(a, tile_start, tile);
         const PlanDev* P = a.plans + tr.plan;
         const int key = __builtin_amdgcn_readfirstlane(P->enc_wc * 100 + P->enc_ntw);
         switch (key) {
 #define KVTC_CASE(WC, NTW) case (WC) * 100 + (NTW): encode_tile<NTW, WC, XT>(P, tr, a, work); break;
-            KVTC_CASE(1, 2) KVTC_CASE(1, 4) KVTC_CASE(1, 6) KVTC_CASE(1, 8) KVTC_CASE(1, 10)
-            KVTC_CASE(2, 6) KVTC_CASE(2, 8) KVTC_CASE(2, 10)
-            KVTC_CASE(4, 6) KVTC_CASE(4, 8)
+            KVTC_CASE(1, 2) KVTC_CASE(1, 4) KVTC_CASE(2, 3) KVTC_CASE(2, 4) KVTC_CASE(2, 5)
 #undef KVTC_CASE
             default: break;
         }
     }
 }
 
-hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int grid, size_t lds_bytes, hipStream_t stream) {
+template <typename XT>
+__global__ void __launch_bounds__(kThreads, 1) kvtc_encode_wide_kernel(const KernelArgs a) {
+    extern __shared__ uint4 smem[];
+    uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
+    uint4* work = smem + kJobTableBytes / 16 + 1;
+    const uint32_t total = build_tile_table<true, 1>(a, tile_start, reinterpret_cast<uint32_t*>(work));
+    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
+        const TileRef tr = find_tile(a, tile_start, tile);
+        const PlanDev* P = a.plans + tr.plan;
+        const int key = __builtin_amdgcn_readfirstlane(P->enc_wc * 100 + P->enc_ntw);
+        switch (key) {
+#define KVTC_CASE(WC, NTW) case (WC) * 100 + (NTW): encode_tile<NTW, WC, XT>(P, tr, a, work); break;
+            KVTC_CASE(2, 6) KVTC_CASE(2, 8) KVTC_CASE(2, 10) KVTC_CASE(4, 6) KVTC_CASE(4, 8)
+#undef KVTC_CASE
+            default: break;
+        }
+    }
+}
+
+template <typename K>
+static hipError_t set_lds_attr(K kernel) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+}
+
+// wide = 0: the two-waves-per-SIMD kernel, 1: the 512-register kernel.
+hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kvtc_encode_kernel<uint16_t>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kvtc_encode_kernel<float>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+        hipError_t e = set_lds_attr(&kvtc_encode_kernel<uint16_t>);
+        if (e == hipSuccess) e = set_lds_attr(&kvtc_encode_kernel<float>);
+        if (e == hipSuccess) e = set_lds_attr(&kvtc_encode_wide_kernel<uint16_t>);
+        if (e == hipSuccess) e = set_lds_attr(&kvtc_encode_wide_kernel<float>);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    if (dtype == KVTC_BF16)
-        hipLaunchKernelGGL(kvtc_encode_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
-    else
-        hipLaunchKernelGGL(kvtc_encode_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+    if (!wide) {
+        if (dtype == KVTC_BF16)
+            hipLaunchKernelGGL(kvtc_encode_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+        else
+            hipLaunchKernelGGL(kvtc_encode_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+    } else {
+        if (dtype == KVTC_BF16)
+            hipLaunchKernelGGL(kvtc_encode_wide_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+        else
+            hipLaunchKernelGGL(kvtc_encode_wide_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
+    }
     return hipGetLastError();
+}
+
+// LDS bytes encode_tile needs for a variant (main loop slabs vs epilogue images).
+int encode_lds_bytes(int ntw, int wc, int n_groups, int rec_dwords, kvtc_dtype dtype) {
+    const int ntp = ntw * wc;
+    const int ks = dtype == KVTC_BF16 ? enc_ks<uint16_t>(ntp) : enc_ks<float>(ntp);
+    const int tok_wg = 64 * (4 / wc);
+    const int main_b = 2 * ks * ntp * 1024;
+    const int epi_b = tok_wg * (2 * ntp * 8 + n_groups * 8 + (rec_dwords + 1) * 4);
+    return main_b > epi_b ? main_b : epi_b;
 }
 
 }  // namespace kvtc
