@@ -144,11 +144,22 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
     __syncthreads();          // record image is dead; the slabs reuse its space
 
     // ---- sweep the feature tiles --------------------------------------------------------
-    uint4* slab0 = smem;
-    uint4* slab1 = smem + SLAB_U4;
+    // LDS ring of NSTAGE basis slabs (one 32-feature tile each), filled by asynchronous
+    // global->LDS transfers issued NSTAGE-1 tiles ahead.
+    constexpr int NSTAGE = NCT <= 10 ? 3 : 2;
+    constexpr int D = NSTAGE - 1;
+    constexpr int NV = SLAB_U4 / kThreads;
+    static_assert(SLAB_U4 % kThreads == 0 && 3 * NV < 64, "whole transfers, vmcnt range");
     const uint4* vg = P->v_dec;
     const int n_ft = p / 32;
-    dma_slab<SLAB_U4>(vg, slab0, wave, lane);
+    const uint32_t lds_ring = lds_offset(smem);
+    auto issue = [&](int ft, int stage) {
+        const uint4* vsrc = vg + (size_t)ft * SLAB_U4 + wave * 64 + lane;
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            dma16_async(vsrc + i * kThreads,
+                        __builtin_amdgcn_readfirstlane(lds_ring + (stage * SLAB_U4 + i * kThreads + wave * 64) * 16));
+    };
 
     OT* orow[TT];
     bool valid[TT];
@@ -158,14 +169,20 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
         valid[tt] = t < T;
         orow[tt] = reinterpret_cast<OT*>(const_cast<void*>(a.x)) + (tr.x_row0 + (valid[tt] ? t : 0)) * a.ld_x + 16 * h;
     }
-    const float* mu = P->mu + 16 * h;
-    wait_vmem_all();
+    // mu sits in LDS behind the ring: a global load inside the loop would make the compiler
+    // wait for everything in flight, the asynchronous transfers included
+    float* mu_lds = reinterpret_cast<float*>(smem + NSTAGE * SLAB_U4);
+    for (int i = tid; i < p; i += kThreads) mu_lds[i] = P->mu[i];
+    const float* mu = mu_lds + 16 * h;
+
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < n_ft) issue(u, u);
+    wait_vmem_times<NV>(min(D - 1, n_ft - 1));
     __syncthreads();
 
-    for (int ft = 0; ft < n_ft; ++ft) {
-        const uint4* cur = (ft & 1) ? slab1 : slab0;
-        uint4* nxt = (ft & 1) ? slab0 : slab1;
-        const bool more = ft + 1 < n_ft;
+    auto tile_step = [&](int ft, int stage) {
+        if (ft + D < n_ft) issue(ft + D, (stage + D) % NSTAGE);
         f32x16 acc[TT];
         {
             f32x16 m;
@@ -178,7 +195,7 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
             for (int tt = 0; tt < TT; ++tt) acc[tt] = m;
         }
         constexpr int NSTEP = 2 * NCT;
-        const uint4* abase = cur + lane;
+        const uint4* abase = smem + stage * SLAB_U4 + lane;
         uint4 af[3];
         af[0] = abase[0];
         af[1] = abase[64];
@@ -186,11 +203,6 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
 #pragma unroll
         for (int ks = 0; ks < NSTEP; ++ks) {
             if (ks + 2 < NSTEP) af[(ks + 2) % 3] = abase[(ks + 2) * 64];
-            if (ks + 2 == NSTEP - 1) {          // last LDS read of this tile is out: start the next slab
-                __builtin_amdgcn_sched_barrier(0);
-                if (more) dma_slab<SLAB_U4>(vg + (size_t)(ft + 1) * SLAB_U4, nxt, wave, lane);
-                __builtin_amdgcn_sched_barrier(0);
-            }
             const bf16x8 av = as_bf16x8_d(af[ks % 3]);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
@@ -200,11 +212,17 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
         OutRegs<OT> o[TT];
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) o[tt].set(acc[tt]);
-        wait_vmem_all();
+        // leaves only the younger basis stages in flight (the previous tile's stores are older)
+        wait_vmem_times<NV>(min(D - 1, n_ft - 2 - ft));
         __syncthreads();
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
             if (valid[tt]) o[tt].store(orow[tt] + ft * 32);
+    };
+    for (int f0 = 0; f0 < n_ft; f0 += NSTAGE) {
+#pragma unroll
+        for (int u = 0; u < NSTAGE; ++u)
+            if (f0 + u < n_ft) tile_step(f0 + u, u);
     }
     __syncthreads();
 }
@@ -278,10 +296,10 @@ hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int gr
     return hipGetLastError();
 }
 
-int decode_lds_bytes(int nct, int tt, int rec_dwords) {
+int decode_lds_bytes(int nct, int tt, int rec_dwords, int p) {
     const int tok_wg = 4 * 32 * tt;
     const int rec_b = tok_wg * (rec_dwords + 1) * 4;
-    const int slab_b = 2 * 2 * nct * 1024;
+    const int slab_b = (nct <= 10 ? 3 : 2) * 2 * nct * 1024 + p * 4;
     return rec_b > slab_b ? rec_b : slab_b;
 }
 

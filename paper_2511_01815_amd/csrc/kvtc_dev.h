@@ -20,9 +20,8 @@ struct PlanDev {
     int32_t enc_ntw, enc_wc;                // encode variant: coefficient tiles per wave, waves across coefficients
     int32_t dec_nct, dec_tt;                // decode variant: coefficient tiles, token tiles per wave
     int32_t enc_tok_wg, dec_tok_wg;         // tokens per workgroup tile
-    int32_t enc_lds, dec_lds;               // dynamic LDS bytes needed (without the job table)
+    int32_t enc_lds[2], dec_lds;            // dynamic LDS bytes needed (without the job table); encode: per input dtype
     int32_t enc_wide, dec_wide;             // 0: served by the two-waves-per-SIMD kernel, 1: by the 512-register one
-    int32_t pad_;
     const uint4* v_enc;    // [p/16][32*ntp/32][64] MFMA A fragments of V_kept^T (encode)
     const uint4* v_dec;    // [p/32][2*nct][64]     MFMA A fragments of V_kept   (decode)
     const float* negc;     // [32*ntp]  -(mu^T V_kept), zero in the padding
@@ -153,6 +152,32 @@ __device__ __forceinline__ void dma_slab(const uint4* __restrict__ src, uint4* d
         dma16(src + i * kThreads + wave * 64 + lane, dst + i * kThreads + wave * 64);
 }
 
-__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+// LDS byte offset of a pointer into shared memory.
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+    return (uint32_t)(size_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+// The same transfer issued behind the compiler's back: it neither orders later LDS reads after
+// it nor counts it, so a step's transfers can stay in flight while the previous slab is read.
+// The caller owns the wait: wait_vmem_all() before the barrier that publishes the data.
+// lds_byte_addr must be wave-uniform (it goes through M0).
+__device__ __forceinline__ void dma16_async(const void* gsrc, uint32_t lds_byte_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gsrc), "s"(lds_byte_addr) : "memory");
+}
+
+// s_waitcnt vmcnt(N) only (N <= 63): the N most recent vector-memory operations may stay in flight.
+template <int N> __device__ __forceinline__ void wait_vmem() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wait_vmem_all() { wait_vmem<0>(); }
+// Wait until at most k * N operations are in flight, k in 0..3 chosen at run time (wave-uniform).
+template <int N> __device__ __forceinline__ void wait_vmem_times(int k) {
+    if (k <= 0) wait_vmem<0>();
+    else if (k == 1) wait_vmem<N>();
+    else if (k == 2) wait_vmem<2 * N>();
+    else wait_vmem<3 * N>();
+}
 
 }  // namespace kvtc

@@ -31,21 +31,28 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// 8 consecutive features of one token as a B-operand fragment.
-template <typename XT> struct XFrag;
-template <> struct XFrag<uint16_t> {       // bf16 input
-    uint4 v;
-    __device__ __forceinline__ void load(const uint16_t* p) { v = *reinterpret_cast<const uint4*>(p); }
-    __device__ __forceinline__ bf16x8 get() const { return as_bf16x8(v); }
-};
-template <> struct XFrag<float> {          // fp32 input, rounded to bf16 (nearest even) on use
-    float4 a, b;
-    __device__ __forceinline__ void load(const float* p) {
-        a = *reinterpret_cast<const float4*>(p);
-        b = *reinterpret_cast<const float4*>(p + 4);
+// The X slab of one step in LDS: TOK rows of KS*16 features, written by global->LDS transfers
+// in 16-byte columns.  Column c of row r is stored at column c ^ swz(r) so that the 8 lanes
+// served together by a 128-bit LDS read (8 consecutive tokens, same column) fall on 8 different
+// 16-byte bank groups.
+template <typename XT, int KS> struct XSlab;
+template <int KS> struct XSlab<uint16_t, KS> {                 // bf16 input: KS*32 bytes per row
+    static constexpr int ROW_B = KS * 32, COLS = ROW_B / 16, ROWS_PER_DMA = 64 / COLS;
+    static __device__ __forceinline__ int swz(int r) { return (r * COLS / 8) & (COLS - 1); }
+    // B fragment of (row, k-step, lane half): 8 consecutive features
+    static __device__ __forceinline__ bf16x8 frag(const char* slab, int row, int ks, int h) {
+        const int c = (2 * ks + h) ^ swz(row);
+        return as_bf16x8(*reinterpret_cast<const uint4*>(slab + row * ROW_B + c * 16));
     }
-    __device__ __forceinline__ bf16x8 get() const {
-        bf16x8 r;
+};
+template <int KS> struct XSlab<float, KS> {                    // fp32 input: KS*64 bytes per row
+    static constexpr int ROW_B = KS * 64, COLS = ROW_B / 16, ROWS_PER_DMA = 64 / COLS;
+    static __device__ __forceinline__ int swz(int r) { return (r * COLS / 8) & (COLS - 1); }
+    static __device__ __forceinline__ bf16x8 frag(const char* slab, int row, int ks, int h) {
+        const int c0 = (4 * ks + 2 * h) ^ swz(row), c1 = (4 * ks + 2 * h + 1) ^ swz(row);
+        const float4 a = *reinterpret_cast<const float4*>(slab + row * ROW_B + c0 * 16);
+        const float4 b = *reinterpret_cast<const float4*>(slab + row * ROW_B + c1 * 16);
+        bf16x8 r;                                                // round to bf16, nearest even
         r[0] = (__bf16)a.x; r[1] = (__bf16)a.y; r[2] = (__bf16)a.z; r[3] = (__bf16)a.w;
         r[4] = (__bf16)b.x; r[5] = (__bf16)b.y; r[6] = (__bf16)b.z; r[7] = (__bf16)b.w;
         return r;
@@ -59,10 +66,11 @@ __device__ __forceinline__ void put_bits(uint32_t* rec, uint32_t pos, uint32_t v
     if (s + len > 32u) atomicOr(rec + dw + 1, v >> (32u - s));
 }
 
-// k-steps (16 features each) per LDS slab of the basis
-template <typename XT> __host__ __device__ constexpr int enc_ks(int ntp) {
-    return sizeof(XT) == 2 ? (ntp <= 8 ? 4 : 2) : 2;
-}
+// k-steps (16 features each) per pipeline stage, and stages in the LDS ring.  Sized so that a
+// narrow plan (<= 10 coordinate tiles, two workgroups per compute unit) stays within ~72 KB
+// and a wide one (one workgroup) within ~150 KB.
+__host__ __device__ constexpr int enc_ks(int ntp) { return ntp <= 8 || (ntp > 10 && ntp <= 16) ? 2 : 1; }
+__host__ __device__ constexpr int enc_stages(int ntp) { return enc_ks(ntp) == 2 ? 3 : 4; }
 
 template <int NTW, int WC, typename XT>
 __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const TileRef& tr,
@@ -71,7 +79,8 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
     constexpr int NTP = NTW * WC;            // coordinate tiles of the padded plan
     constexpr int WT = 4 / WC;               // waves across tokens
     constexpr int TOK_WG = 64 * WT;
-    constexpr int KS = enc_ks<XT>(NTP);
+    constexpr int KS = enc_ks(NTP);
+    constexpr int NSTAGE = enc_stages(NTP);
     constexpr int SLAB_U4 = KS * NTP * 64;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -81,14 +90,7 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
     const int T = tr.n_tokens;
     const int tok_tile0 = tr.tile * TOK_WG;
 
-    // ---- operands ---------------------------------------------------------------
-    const XT* xrow[TT];
-#pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        int t = tok_tile0 + wt * 64 + tt * 32 + l32;
-        t = t < T ? t : T - 1;                                   // tail: re-read the last row
-        xrow[tt] = reinterpret_cast<const XT*>(a.x) + (tr.x_row0 + t) * a.ld_x + 8 * h;
-    }
+    // ---- accumulators start at -(mu^T V_kept): centring folded into the product ------
     f32x16 acc[TT][NTW];
     {
         const float* negc = P->negc + (wc * NTW) * 32 + 16 * h;
@@ -105,41 +107,60 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
         }
     }
 
-    uint4* slab0 = smem;
-    uint4* slab1 = smem + SLAB_U4;
+    // ---- LDS: a ring of NSTAGE stages, each one basis slab and one X slab ----------
+    using XS = XSlab<XT, KS>;
+    constexpr int XSLAB_B = TOK_WG * XS::ROW_B;
+    constexpr int STAGE_B = SLAB_U4 * 16 + XSLAB_B;
+    constexpr int NX_TOTAL = TOK_WG / XS::ROWS_PER_DMA;         // X transfers per stage, dealt round-robin to the waves
+    constexpr int NXD = (NX_TOTAL + 3) / 4;
+    constexpr int NV_TOTAL = SLAB_U4 / 64;                      // basis transfers per stage (1 KB each), dealt the same way
+    constexpr int NV = (NV_TOTAL + 3) / 4;
+    constexpr int NDMA_MIN = NV_TOTAL / 4 + NX_TOTAL / 4;       // transfers per wave per stage, lower bound over waves
+    static_assert(TOK_WG % XS::ROWS_PER_DMA == 0, "whole transfers");
+    static_assert(3 * (NV + NXD) < 64, "vmcnt range");
+    char* ring = reinterpret_cast<char*>(smem);
     const uint4* vg = P->v_enc;
-    const int n_slabs = p / (16 * KS);          // p is a multiple of 64 = 16 * max KS
+    const int n_slabs = p / (16 * KS);
 
-    XFrag<XT> xa[TT][KS], xb[TT][KS];
+    // per-lane source of each X transfer: row (clamped at the tensor's end) and swizzled column
+    const char* xsrc[NXD];
+    uint32_t xdst[NXD];                                         // wave-uniform LDS byte offsets inside an X slab
+#pragma unroll
+    for (int j = 0; j < NXD; ++j) {
+        const int row0 = (j * 4 + wave) * XS::ROWS_PER_DMA;
+        const int row = row0 + lane / XS::COLS;
+        const int col = (lane % XS::COLS) ^ XS::swz(row);
+        int t = tok_tile0 + row;
+        t = t < T ? t : T - 1;                                  // tail rows re-read the last token
+        xsrc[j] = reinterpret_cast<const char*>(reinterpret_cast<const XT*>(a.x) + (tr.x_row0 + t) * a.ld_x) + col * 16;
+        xdst[j] = (uint32_t)(SLAB_U4 * 16 + row0 * XS::ROW_B);
+    }
+    const uint32_t lds_ring = lds_offset(ring);
 
-    // prologue: slab 0 -> LDS (no register staging), first X batch -> registers
-    dma_slab<SLAB_U4>(vg, slab0, wave, lane);
+    // All global traffic of the main loop is asynchronous global->LDS transfers issued
+    // NSTAGE-1 steps ahead; the only wait is the one in front of the barrier that publishes
+    // the next stage, and it leaves the younger stages in flight.
+    auto issue = [&](int s, int stage) {
+        const uint32_t base = lds_ring + stage * STAGE_B;
+        const uint4* vsrc = vg + (size_t)s * SLAB_U4 + wave * 64 + lane;
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt)
+        for (int i = 0; i < NV; ++i)
+            if (i * 4 + wave < NV_TOTAL)
+                dma16_async(vsrc + i * kThreads, __builtin_amdgcn_readfirstlane(base + (i * kThreads + wave * 64) * 16));
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) xa[tt][ks].load(xrow[tt] + ks * 16);
-    wait_vmem_all();
-    __syncthreads();
-
-    // One slab step.  The X fragments of the next step are requested first (a whole step of
-    // latency cover); the A fragments come from LDS two MFMA groups ahead; the next slab's
-    // global->LDS transfer is issued right after this step's last LDS read, because the
-    // compiler orders every later LDS read behind an outstanding transfer.
-    auto slab_step = [&](const uint4* cur, uint4* nxt, XFrag<XT> (&xc)[TT][KS], XFrag<XT> (&xn)[TT][KS], int s) {
-        const bool more = s + 1 < n_slabs;
-        if (more) {
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) xn[tt][ks].load(xrow[tt] + (s + 1) * KS * 16 + ks * 16);
-        }
+        for (int j = 0; j < NXD; ++j)
+            if (j * 4 + wave < NX_TOTAL)
+                dma16_async(xsrc[j] + (size_t)s * XS::ROW_B, __builtin_amdgcn_readfirstlane(base + xdst[j]));
+    };
+    auto compute = [&](int stage) {
+        const uint4* abase = reinterpret_cast<const uint4*>(ring + stage * STAGE_B) + (wc * NTW) * 64 + lane;
+        const char* xs = ring + stage * STAGE_B + SLAB_U4 * 16;
         constexpr int NSTEP = KS * NTW;
-        bf16x8 xv[TT][KS];
+        bf16x8 xv[KS][TT];
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) xv[tt][ks] = xc[tt][ks].get();
-        const uint4* abase = cur + (wc * NTW) * 64 + lane;
+            for (int tt = 0; tt < TT; ++tt) xv[ks][tt] = XS::frag(xs, wt * 64 + tt * 32 + l32, ks, h);
         uint4 af[3];
         af[0] = abase[0];
         if (NSTEP > 1) af[1] = abase[((1 / NTW) * NTP + (1 % NTW)) * 64];
@@ -148,23 +169,32 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
         for (int j = 0; j < NSTEP; ++j) {
             const int ks = j / NTW, ct = j % NTW;
             if (j + 2 < NSTEP) af[(j + 2) % 3] = abase[(((j + 2) / NTW) * NTP + ((j + 2) % NTW)) * 64];
-            if (j + 2 == NSTEP - 1) {
-                __builtin_amdgcn_sched_barrier(0);
-                if (more) dma_slab<SLAB_U4>(vg + (size_t)(s + 1) * SLAB_U4, nxt, wave, lane);
-                __builtin_amdgcn_sched_barrier(0);
-            }
             const bf16x8 av = as_bf16x8(af[j % 3]);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
-                acc[tt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, xv[tt][ks], acc[tt][ct], 0, 0, 0);
+                acc[tt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, xv[ks][tt], acc[tt][ct], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        wait_vmem_all();
-        __syncthreads();
     };
-    for (int s = 0; s < n_slabs; s += 2) {
-        slab_step(slab0, slab1, xa, xb, s);
-        if (s + 1 < n_slabs) slab_step(slab1, slab0, xb, xa, s + 1);
+
+    constexpr int D = NSTAGE - 1;                               // prefetch distance in steps
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < n_slabs) issue(u, u);
+    wait_vmem_times<NDMA_MIN>(min(D - 1, n_slabs - 1));         // stage 0 has landed
+    __syncthreads();
+    for (int s0 = 0; s0 < n_slabs; s0 += NSTAGE) {
+#pragma unroll
+        for (int u = 0; u < NSTAGE; ++u) {
+            const int s = s0 + u;
+            if (s < n_slabs) {
+                // stage (u + D) % NSTAGE was read in step s - 1; the barrier that ended it frees it
+                if (s + D < n_slabs) issue(s + D, (u + D) % NSTAGE);
+                compute(u);
+                wait_vmem_times<NDMA_MIN>(min(D - 1, n_slabs - 2 - s));   // stage of step s + 1 has landed
+                __syncthreads();
+            }
+        }
     }
 
     // ---- epilogue -----------------------------------------------------------------
@@ -341,9 +371,9 @@ hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int wide, int gr
 // LDS bytes encode_tile needs for a variant (main loop slabs vs epilogue images).
 int encode_lds_bytes(int ntw, int wc, int n_groups, int rec_dwords, kvtc_dtype dtype) {
     const int ntp = ntw * wc;
-    const int ks = dtype == KVTC_BF16 ? enc_ks<uint16_t>(ntp) : enc_ks<float>(ntp);
+    const int ks = enc_ks(ntp);
     const int tok_wg = 64 * (4 / wc);
-    const int main_b = 2 * ks * ntp * 1024;
+    const int main_b = enc_stages(ntp) * (ks * ntp * 1024 + tok_wg * ks * (dtype == KVTC_BF16 ? 32 : 64));
     const int epi_b = tok_wg * (2 * ntp * 8 + n_groups * 8 + (rec_dwords + 1) * 4);
     return main_b > epi_b ? main_b : epi_b;
 }
