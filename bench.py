@@ -75,6 +75,8 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=32768)
     ap.add_argument("--cpu-tokens", type=int, default=32768, help="tokens per tensor in the CPU-baseline sample")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-check", action="store_true",
+                    help="also run one plain device copy of the whole input (known size) for scaling profiler byte counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards with no exchange step; "
@@ -137,6 +139,11 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     assert status.cpu().tolist() == [0, 0], "a job was skipped"
+    if args.copy_check:        # 2 * raw bytes of traffic in one elementwise copy kernel
+        scratch = torch.empty_like(x)
+        scratch.copy_(x)
+        torch.cuda.synchronize()
+        del scratch
     assert int(offs[-1].item()) == cap
 
     enc_ms = [ev[4 * i].elapsed_time(ev[4 * i + 1]) for i in range(args.warmup, args.warmup + args.steps)]
