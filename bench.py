@@ -170,7 +170,12 @@ def main() -> int:
     else:
         roof = dict(bound="mfma", achieved=flops / (dom_ms * 1e-3) / 1e12, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    # HBM bytes per launch of that kernel from rocprofv3 TCC counters (FETCH_SIZE + WRITE_SIZE, each scaled by
+    # what the same counter reads for a 4 GiB copy): measured offline on the default workload only,
+    # see profiles/kvtc_kernels_c2x32_cr16.md
+    measured = {"kvtc_encode_kernel": 4.58 * 2**30, "kvtc_decode_kernel": 5.67 * 2**30}
+    default_workload = args.cr == 16 and NL == 32 and T == 32768
+    roof["traffic"] = measured[dom] if default_workload else None
     roof["kernel"] = dom
     roof["encode"] = dict(ms=enc_avg, raw_GBps=raw_bytes / enc_avg / 1e6,
                           hbm_frac=alg_bytes / (enc_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
