@@ -17,7 +17,7 @@ namespace kvtc {
 hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream);
 hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream);
 int encode_lds_bytes(int ntw, int wc, int n_groups, int rec_dwords, kvtc_dtype dtype);
-int decode_lds_bytes(int nct, int tt, int rec_dwords, int p);
+int decode_lds_bytes(int nct, int tt, int rec_dwords, int p, kvtc_dtype dtype);
 }  // namespace kvtc
 
 using namespace kvtc;
@@ -32,7 +32,7 @@ struct kvtc_plan {
 struct kvtc_batch {
     PlanDev* plans_dev;
     int n_plans;
-    int enc_lds[2][2], dec_lds[2];   // max over the plans of each kernel flavour (narrow, wide) [and input dtype]; -1: none
+    int enc_lds[2][2], dec_lds[2][2];   // max over the plans of each kernel flavour (narrow, wide) and element dtype; -1: none
     int max_p;
     std::vector<int32_t> rec_dwords;
     uint32_t* rec_dwords_dev;
@@ -186,13 +186,14 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     {
         d.enc_lds[KVTC_BF16] = encode_lds_bytes(d.enc_ntw, d.enc_wc, n_groups, d.rec_dwords, KVTC_BF16);
         d.enc_lds[KVTC_F32] = encode_lds_bytes(d.enc_ntw, d.enc_wc, n_groups, d.rec_dwords, KVTC_F32);
-        d.dec_lds = decode_lds_bytes(d.dec_nct, d.dec_tt, d.rec_dwords, p);
+        d.dec_lds[KVTC_BF16] = decode_lds_bytes(d.dec_nct, d.dec_tt, d.rec_dwords, p, KVTC_BF16);
+        d.dec_lds[KVTC_F32] = decode_lds_bytes(d.dec_nct, d.dec_tt, d.rec_dwords, p, KVTC_F32);
     }
     const int lds_cap = kLdsBudget - kJobTableBytes - 64;
-    if (d.enc_lds[0] > lds_cap || d.enc_lds[1] > lds_cap || d.dec_lds > lds_cap)
+    if (d.enc_lds[0] > lds_cap || d.enc_lds[1] > lds_cap || d.dec_lds[0] > lds_cap || d.dec_lds[1] > lds_cap)
         return fail(KVTC_E_UNSUPPORTED,
                     "kvtc_plan_create: record of %d bytes with r=%d needs %d/%d/%d bytes of LDS, %d available",
-                    d.rec_dwords * 4, r, d.enc_lds[0], d.enc_lds[1], d.dec_lds, lds_cap);
+                    d.rec_dwords * 4, r, d.enc_lds[0], d.enc_lds[1], d.dec_lds[0], lds_cap);
 
     // ---- host images ---------------------------------------------------------------
     const size_t n_venc = (size_t)(p / 16) * ntp * 64 * 8;      // bf16 elements
@@ -371,7 +372,7 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
     const int64_t tiles = (n_tokens + plan->h.dec_tok_wg - 1) / plan->h.dec_tok_wg;
     const int slots = cu_count() * (plan->h.dec_wide ? 1 : 2);
     const int grid = (int)(tiles < slots ? tiles : slots);
-    hipError_t e = launch_decode(a, dtype, plan->h.dec_wide, grid, (size_t)kJobTableBytes + 64 + plan->h.dec_lds, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_decode(a, dtype, plan->h.dec_wide, grid, (size_t)kJobTableBytes + 64 + plan->h.dec_lds[dtype], static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }
@@ -385,7 +386,8 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
     b->plans_dev = nullptr;
     b->rec_dwords_dev = nullptr;
     b->n_plans = n_plans;
-    b->enc_lds[0][0] = b->enc_lds[0][1] = b->enc_lds[1][0] = b->enc_lds[1][1] = b->dec_lds[0] = b->dec_lds[1] = -1;
+    for (int f = 0; f < 2; ++f)
+        for (int dt = 0; dt < 2; ++dt) b->enc_lds[f][dt] = b->dec_lds[f][dt] = -1;
     b->max_p = 0;
     for (int i = 0; i < n_plans; ++i) {
         if (!plans[i]) {
@@ -397,7 +399,8 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
         const PlanDev& ph = plans[i]->h;
         for (int dt = 0; dt < 2; ++dt)
             if (ph.enc_lds[dt] > b->enc_lds[ph.enc_wide][dt]) b->enc_lds[ph.enc_wide][dt] = ph.enc_lds[dt];
-        if (ph.dec_lds > b->dec_lds[ph.dec_wide]) b->dec_lds[ph.dec_wide] = ph.dec_lds;
+        for (int dt = 0; dt < 2; ++dt)
+            if (ph.dec_lds[dt] > b->dec_lds[ph.dec_wide][dt]) b->dec_lds[ph.dec_wide][dt] = ph.dec_lds[dt];
         if (ph.p > b->max_p) b->max_p = ph.p;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -504,9 +507,9 @@ kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.status = status_dev;
     if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_decode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
     for (int wide = 0; wide < 2; ++wide) {
-        if (batch->dec_lds[wide] < 0) continue;
+        if (batch->dec_lds[wide][dtype] < 0) continue;
         hipError_t e = launch_decode(a, dtype, wide, cu_count() * (wide ? 1 : 2),
-                                     (size_t)kJobTableBytes + 64 + batch->dec_lds[wide], static_cast<hipStream_t>(stream));
+                                     (size_t)kJobTableBytes + 64 + batch->dec_lds[wide][dtype], static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode_batch: launch failed: %s", hipGetErrorString(e));
     }
     return KVTC_OK;

@@ -29,31 +29,43 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
-// Output registers of one (token tile, feature tile): converted before the workgroup barrier,
-// stored after it, so the stores have a whole step to drain before the next full wait.
-template <typename OT> struct OutRegs;
-template <> struct OutRegs<uint16_t> {
+// Output staging.  A lane holds 16 consecutive features of ONE token per (token tile, feature
+// tile); storing that directly scatters 16-byte pieces over 32 rows per instruction, and stores
+// narrower than a 128-byte line run at a fraction of the write bandwidth (measured on MI355X:
+// 16 B pieces 1.3 TB/s, 64 B 3.5 TB/s, whole lines 5.6 TB/s).  Each wave therefore transposes
+// through a private LDS tile [tokens][128 bytes] -- one feature tile of fp32 output, two of bf16
+// output: lanes write their pieces (16-byte columns, XOR-swizzled against bank conflicts), then
+// read back so that 8 consecutive lanes cover one row's 128 bytes, and store whole lines.
+template <typename OT> struct OutStage {
+    static constexpr int ROW_B = 128;
+    static constexpr int FT_PER_ROW = ROW_B / (32 * (int)sizeof(OT));   // feature tiles per line: 2 (bf16), 1 (fp32)
+    static constexpr int COLS = ROW_B / 16;                    // 16-byte columns per row
+    static constexpr int RPI = 64 / COLS;                      // rows per store instruction
+    static __device__ __forceinline__ int swz(int r) { return r & 7; }
+};
+// `half` = feature tile parity (which 32 of the 64 features)
+__device__ __forceinline__ void stage_put(char* st, int row, int h, int half, const f32x16& v, uint16_t) {
+    using S = OutStage<uint16_t>;
     uint4 a, b;
-    __device__ __forceinline__ void set(const f32x16& v) {
-        a.x = pack_bf16x2(v[0], v[1]);   a.y = pack_bf16x2(v[2], v[3]);
-        a.z = pack_bf16x2(v[4], v[5]);   a.w = pack_bf16x2(v[6], v[7]);
-        b.x = pack_bf16x2(v[8], v[9]);   b.y = pack_bf16x2(v[10], v[11]);
-        b.z = pack_bf16x2(v[12], v[13]); b.w = pack_bf16x2(v[14], v[15]);
-    }
-    __device__ __forceinline__ void store(uint16_t* p) const {
-        reinterpret_cast<uint4*>(p)[0] = a;
-        reinterpret_cast<uint4*>(p)[1] = b;
-    }
-};
-template <> struct OutRegs<float> {
-    f32x16 v;
-    __device__ __forceinline__ void set(const f32x16& x) { v = x; }
-    __device__ __forceinline__ void store(float* p) const {
+    a.x = pack_bf16x2(v[0], v[1]);   a.y = pack_bf16x2(v[2], v[3]);
+    a.z = pack_bf16x2(v[4], v[5]);   a.w = pack_bf16x2(v[6], v[7]);
+    b.x = pack_bf16x2(v[8], v[9]);   b.y = pack_bf16x2(v[10], v[11]);
+    b.z = pack_bf16x2(v[12], v[13]); b.w = pack_bf16x2(v[14], v[15]);
+    char* r = st + row * S::ROW_B;
+    const int c = 4 * half + 2 * h;
+    *reinterpret_cast<uint4*>(r + ((c ^ S::swz(row)) * 16)) = a;
+    *reinterpret_cast<uint4*>(r + (((c + 1) ^ S::swz(row)) * 16)) = b;
+}
+__device__ __forceinline__ void stage_put(char* st, int row, int h, int half, const f32x16& v, float) {
+    using S = OutStage<float>;
+    char* r = st + row * S::ROW_B;
+    const int c = 4 * h;        // one feature tile fills the line
+    (void)half;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            reinterpret_cast<float4*>(p)[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
-    }
-};
+    for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(r + (((c + q) ^ S::swz(row)) * 16)) =
+            make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+}
 
 template <int NCT, int TT, typename OT>
 __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const TileRef& tr,
@@ -82,11 +94,16 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
             const uint32_t t = __umulhi((uint32_t)i, magic);
             rec[t * rstride + ((uint32_t)i - t * rd)] = in[i];
         }
-        // rows of tokens past the end of the tensor and the pad dwords: defined contents
+        // pad dwords: defined contents.  Rows past the end of the tensor replicate the last token's
+        // record, so every lane decodes something valid and the tail lanes store the same bytes to
+        // the same place as the last token's lane: no store is ever predicated off, which keeps the
+        // number of memory operations per step fixed (the explicit vmcnt waits count on it).
         for (int i = tid; i < TOK_WG; i += kThreads) rec[i * rstride + rd] = 0u;
+        const uint32_t* last = in + (size_t)(n_valid - 1) * rd;
         for (int i = total + tid; i < TOK_WG * rd; i += kThreads) {
             const uint32_t t = __umulhi((uint32_t)i, magic);
-            rec[t * rstride + ((uint32_t)i - t * rd)] = 0u;
+            const uint32_t w = (uint32_t)i - t * rd;
+            rec[t * rstride + w] = last[w];
         }
     }
     __syncthreads();
@@ -146,10 +163,10 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
     // ---- sweep the feature tiles --------------------------------------------------------
     // LDS ring of NSTAGE basis slabs (one 32-feature tile each), filled by asynchronous
     // global->LDS transfers issued NSTAGE-1 tiles ahead.
-    constexpr int NSTAGE = NCT <= 10 ? 3 : 2;
+    constexpr int NSTAGE = 2;
     constexpr int D = NSTAGE - 1;
     constexpr int NV = SLAB_U4 / kThreads;
-    static_assert(SLAB_U4 % kThreads == 0 && 3 * NV < 64, "whole transfers, vmcnt range");
+    static_assert(SLAB_U4 % kThreads == 0, "whole transfers");
     const uint4* vg = P->v_dec;
     const int n_ft = p / 32;
     const uint32_t lds_ring = lds_offset(smem);
@@ -161,19 +178,25 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
                         __builtin_amdgcn_readfirstlane(lds_ring + (stage * SLAB_U4 + i * kThreads + wave * 64) * 16));
     };
 
-    OT* orow[TT];
-    bool valid[TT];
+    using OS = OutStage<OT>;
+    // store instruction k of a step covers rows k*RPI .. of this wave's 64 tokens; lane -> (row, column)
+    constexpr int NS = TOK_W / OS::RPI;                        // store instructions per PAIR of steps (never predicated off)
+    char* orow[NS];
+    int srow[NS];
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        const int t = tok_tile0 + wave * TOK_W + tt * 32 + l32;
-        valid[tt] = t < T;
-        orow[tt] = reinterpret_cast<OT*>(const_cast<void*>(a.x)) + (tr.x_row0 + (valid[tt] ? t : 0)) * a.ld_x + 16 * h;
+    for (int k = 0; k < NS; ++k) {
+        srow[k] = k * OS::RPI + lane / OS::COLS;
+        int t = tok_tile0 + wave * TOK_W + srow[k];
+        t = t < T ? t : T - 1;                                 // tail: same bytes, same place as the last token
+        orow[k] = reinterpret_cast<char*>(reinterpret_cast<OT*>(const_cast<void*>(a.x)) + (tr.x_row0 + t) * a.ld_x) +
+                  (lane % OS::COLS) * 16;
     }
     // mu sits in LDS behind the ring: a global load inside the loop would make the compiler
     // wait for everything in flight, the asynchronous transfers included
     float* mu_lds = reinterpret_cast<float*>(smem + NSTAGE * SLAB_U4);
     for (int i = tid; i < p; i += kThreads) mu_lds[i] = P->mu[i];
     const float* mu = mu_lds + 16 * h;
+    char* ostage = reinterpret_cast<char*>(mu_lds + p) + wave * (TOK_W * OS::ROW_B);       // this wave's transpose tile
 
 #pragma unroll
     for (int u = 0; u < D; ++u)
@@ -209,15 +232,22 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
                 acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bop[tt][ks], acc[tt], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        OutRegs<OT> o[TT];
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) o[tt].set(acc[tt]);
-        // leaves only the younger basis stages in flight (the previous tile's stores are older)
-        wait_vmem_times<NV>(min(D - 1, n_ft - 2 - ft));
+        for (int tt = 0; tt < TT; ++tt) stage_put(ostage, tt * 32 + l32, h, ft % OS::FT_PER_ROW, acc[tt], OT());
+        // the slab of the next step (issued at the top of this one) must have landed; everything
+        // older -- the previous stores included -- is then complete as well (issue-order completion)
+        wait_vmem<0>();
         __syncthreads();
+        if (ft % OS::FT_PER_ROW == OS::FT_PER_ROW - 1) {
+            // the 128-byte rows are complete: read them back row-contiguous (the
+            // barrier also orders this wave's LDS writes before these reads) and store whole lines
+            uint4 o[NS];
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
-            if (valid[tt]) o[tt].store(orow[tt] + ft * 32);
+            for (int k = 0; k < NS; ++k)
+                o[k] = *reinterpret_cast<const uint4*>(ostage + srow[k] * OS::ROW_B + (((lane % OS::COLS) ^ OS::swz(srow[k])) * 16));
+#pragma unroll
+            for (int k = 0; k < NS; ++k) *reinterpret_cast<uint4*>(orow[k] + (size_t)(ft / OS::FT_PER_ROW) * OS::ROW_B) = o[k];
+        }
     };
     for (int f0 = 0; f0 < n_ft; f0 += NSTAGE) {
 #pragma unroll
@@ -296,10 +326,11 @@ hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int gr
     return hipGetLastError();
 }
 
-int decode_lds_bytes(int nct, int tt, int rec_dwords, int p) {
+int decode_lds_bytes(int nct, int tt, int rec_dwords, int p, kvtc_dtype dtype) {
     const int tok_wg = 4 * 32 * tt;
     const int rec_b = tok_wg * (rec_dwords + 1) * 4;
-    const int slab_b = (nct <= 10 ? 3 : 2) * 2 * nct * 1024 + p * 4;
+    const int slab_b = 2 * 2 * nct * 1024 + p * 4 + tok_wg * 128;
+    (void)dtype;
     return rec_b > slab_b ? rec_b : slab_b;
 }
 

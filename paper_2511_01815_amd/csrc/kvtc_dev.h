@@ -20,7 +20,8 @@ struct PlanDev {
     int32_t enc_ntw, enc_wc;                // encode variant: coefficient tiles per wave, waves across coefficients
     int32_t dec_nct, dec_tt;                // decode variant: coefficient tiles, token tiles per wave
     int32_t enc_tok_wg, dec_tok_wg;         // tokens per workgroup tile
-    int32_t enc_lds[2], dec_lds;            // dynamic LDS bytes needed (without the job table); encode: per input dtype
+    int32_t enc_lds[2], dec_lds[2];         // dynamic LDS bytes needed (without the job table), per element dtype
+    int32_t pad_;
     int32_t enc_wide, dec_wide;             // 0: served by the two-waves-per-SIMD kernel, 1: by the 512-register one
     const uint4* v_enc;    // [p/16][32*ntp/32][64] MFMA A fragments of V_kept^T (encode)
     const uint4* v_dec;    // [p/32][2*nct][64]     MFMA A fragments of V_kept   (decode)
@@ -172,6 +173,17 @@ template <int N> __device__ __forceinline__ void wait_vmem() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 __device__ __forceinline__ void wait_vmem_all() { wait_vmem<0>(); }
+// s_waitcnt vmcnt(n) with a wave-uniform run-time n; n above 31 waits as for 31.
+__device__ __forceinline__ void wait_vmem_dyn(int n) {
+#define KVTC_W(N) case N: wait_vmem<N>(); break;
+    switch (n < 0 ? 0 : (n > 31 ? 31 : n)) {
+        KVTC_W(0) KVTC_W(1) KVTC_W(2) KVTC_W(3) KVTC_W(4) KVTC_W(5) KVTC_W(6) KVTC_W(7)
+        KVTC_W(8) KVTC_W(9) KVTC_W(10) KVTC_W(11) KVTC_W(12) KVTC_W(13) KVTC_W(14) KVTC_W(15)
+        KVTC_W(16) KVTC_W(17) KVTC_W(18) KVTC_W(19) KVTC_W(20) KVTC_W(21) KVTC_W(22) KVTC_W(23)
+        KVTC_W(24) KVTC_W(25) KVTC_W(26) KVTC_W(27) KVTC_W(28) KVTC_W(29) KVTC_W(30) KVTC_W(31)
+    }
+#undef KVTC_W
+}
 // Wait until at most k * N operations are in flight, k in 0..3 chosen at run time (wave-uniform).
 template <int N> __device__ __forceinline__ void wait_vmem_times(int k) {
     if (k <= 0) wait_vmem<0>();
