@@ -96,8 +96,8 @@ size_t kvtc_encoded_bytes(const kvtc_plan* plan, int64_t n_tokens);       /* n_t
 
 /*
  * Encode one tensor (paper, "Compression": project, quantise, pack).
- *   x_dev     [n_tokens][ld_x] elements of `dtype`, row-major, ld_x >= p, 16-byte aligned
- *             base and row pitch.  fp32 inputs are rounded to bf16 (nearest even) on load.
+ *   x_dev     [n_tokens][ld_x] elements of `dtype`, row-major, p <= ld_x <= 2^21, 16-byte
+ *             aligned base and row pitch (a larger pitch is KVTC_E_ARG).  fp32 inputs are rounded to bf16 (nearest even) on load.
  *   out_dev   receives n_tokens records; 16-byte aligned; out_cap >= n_tokens * R else
  *             KVTC_E_SMALL and nothing is written.
  * n_tokens == 0 is KVTC_OK and does nothing.

@@ -64,6 +64,9 @@ int cu_count() {
     return n;
 }
 
+// Row pitch limit (elements): the kernels address a workgroup tile of up to 256 rows with 32-bit byte offsets.
+constexpr int kMaxPitch = 1 << 21;
+
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // position of coordinate/feature row `rho` of an MFMA tile inside the lane's 16 results:
@@ -221,7 +224,8 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     for (int ft = 0; ft < p / 32; ++ft)
         for (int ks = 0; ks < 2 * d.dec_nct; ++ks)
             for (int lane = 0; lane < 64; ++lane) {
-                const int f = 32 * ft + permuted_index(lane & 31);
+                // tiles 2k and 2k+1 hold the even and the odd features of a 64-feature span
+                const int f = 64 * (ft >> 1) + 2 * (lane & 31) + (ft & 1);
                 const int j0 = 32 * (ks >> 1) + 16 * (lane >> 5) + 8 * (ks & 1);
                 uint16_t* dst = &vdec[((((size_t)ft * 2 * d.dec_nct) + ks) * 64 + lane) * 8];
                 for (int e = 0; e < 8; ++e)
@@ -311,6 +315,7 @@ size_t kvtc_encoded_bytes(const kvtc_plan* plan, int64_t n_tokens) {
 static kvtc_status check_x(const char* who, const void* x, kvtc_dtype dtype, int64_t ld_x, int p) {
     if (!dtype_ok(dtype)) return fail(KVTC_E_ARG, "%s: unknown dtype %d", who, (int)dtype);
     if (ld_x < p) return fail(KVTC_E_ARG, "%s: ld_x=%lld < p=%d", who, (long long)ld_x, p);
+    if (ld_x > kMaxPitch) return fail(KVTC_E_ARG, "%s: ld_x=%lld above %d", who, (long long)ld_x, kMaxPitch);
     if ((reinterpret_cast<uintptr_t>(x) & 15u) || ((size_t)ld_x * elem_size(dtype)) % 16 != 0)
         return fail(KVTC_E_ARG, "%s: feature array base and row pitch must be 16-byte aligned", who);
     return KVTC_OK;
@@ -453,6 +458,7 @@ static kvtc_status batch_common(const char* who, const kvtc_batch* batch, const 
     if (!dtype_ok(dtype)) return fail(KVTC_E_ARG, "%s: unknown dtype %d", who, (int)dtype);
     if ((reinterpret_cast<uintptr_t>(x) & 15u) || ((size_t)ld_x * elem_size(dtype)) % 16 != 0 || ld_x <= 0)
         return fail(KVTC_E_ARG, "%s: feature array base and row pitch must be 16-byte aligned", who);
+    if (ld_x > kMaxPitch) return fail(KVTC_E_ARG, "%s: ld_x=%lld above %d", who, (long long)ld_x, kMaxPitch);
     if (reinterpret_cast<uintptr_t>(stream_buf) & 15u) return fail(KVTC_E_ARG, "%s: stream buffer must be 16-byte aligned", who);
     return KVTC_OK;
 }

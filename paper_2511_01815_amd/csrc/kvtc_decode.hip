@@ -2,14 +2,18 @@
 // and dequantised straight into bf16 matrix-core operands, back-projected with V_kept and
 // un-centred, one launch.  (Paper, Section "Method", mode "Decompression"; eq. 3.)
 //
-// X_hat^T = V_kept D_hat^T with the 32x32x16 bf16 MFMA: M = features, N = tokens,
-// K = kept coordinates.  A lane owns one token; its dequantised coordinates ARE its B operand
-// (16 consecutive coordinates = one block of the record = two k-step fragments), so they are
-// built once per tile and stay in registers while the wave sweeps the feature tiles.
-// V_kept is pre-swizzled into A fragments per 32-feature tile, moved global -> LDS without
-// register staging (double-buffered) and shared by the four wavefronts.  Rows of the A operand are permuted
-// so that a lane ends up with 16 consecutive features of its token: 32 contiguous bytes of
-// bf16 output per store pair.
+// X_hat = D_hat V_kept^T with the 32x32x16 bf16 MFMA: M = tokens, N = features,
+// K = kept coordinates.  In the prologue a lane owns one token: its dequantised coordinates ARE
+// its A operand (16 consecutive coordinates = one block of the record = two k-step fragments),
+// built once per tile and kept in registers while the wave sweeps the feature tiles.
+// V_kept is pre-swizzled into B fragments per 32-feature tile, moved global -> LDS without
+// register staging (ring of slabs) and shared by the four wavefronts.  The accumulator then has
+// features across lanes and tokens across registers.  Feature tiles come in pairs that
+// interleave the even and the odd features of a 64-feature span, so a lane packs its two
+// results into one dword (bf16) or one dwordx2 (fp32) and every store instruction writes whole
+// 128-byte lines of two token rows -- no transposition through LDS (measured on MI355X: such
+// dword stores reach the same 5.7 TB/s as 16-byte stores of whole lines, while pieces of
+// 32 bytes per row reach 1.6 TB/s).
 #include <hip/hip_runtime.h>
 #include "kvtc_dev.h"
 #include "kvtc_numeric.h"
@@ -18,6 +22,8 @@ namespace kvtc {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kDecStages = 2;          // basis slabs in the LDS ring
 
 __device__ __forceinline__ bf16x8 as_bf16x8_d(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -29,44 +35,6 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
-// Output staging.  A lane holds 16 consecutive features of ONE token per (token tile, feature
-// tile); storing that directly scatters 16-byte pieces over 32 rows per instruction, and stores
-// narrower than a 128-byte line run at a fraction of the write bandwidth (measured on MI355X:
-// 16 B pieces 1.3 TB/s, 64 B 3.5 TB/s, whole lines 5.6 TB/s).  Each wave therefore transposes
-// through a private LDS tile [tokens][128 bytes] -- one feature tile of fp32 output, two of bf16
-// output: lanes write their pieces (16-byte columns, XOR-swizzled against bank conflicts), then
-// read back so that 8 consecutive lanes cover one row's 128 bytes, and store whole lines.
-template <typename OT> struct OutStage {
-    static constexpr int ROW_B = 128;
-    static constexpr int FT_PER_ROW = ROW_B / (32 * (int)sizeof(OT));   // feature tiles per line: 2 (bf16), 1 (fp32)
-    static constexpr int COLS = ROW_B / 16;                    // 16-byte columns per row
-    static constexpr int RPI = 64 / COLS;                      // rows per store instruction
-    static __device__ __forceinline__ int swz(int r) { return r & 7; }
-};
-// `half` = feature tile parity (which 32 of the 64 features)
-__device__ __forceinline__ void stage_put(char* st, int row, int h, int half, const f32x16& v, uint16_t) {
-    using S = OutStage<uint16_t>;
-    uint4 a, b;
-    a.x = pack_bf16x2(v[0], v[1]);   a.y = pack_bf16x2(v[2], v[3]);
-    a.z = pack_bf16x2(v[4], v[5]);   a.w = pack_bf16x2(v[6], v[7]);
-    b.x = pack_bf16x2(v[8], v[9]);   b.y = pack_bf16x2(v[10], v[11]);
-    b.z = pack_bf16x2(v[12], v[13]); b.w = pack_bf16x2(v[14], v[15]);
-    char* r = st + row * S::ROW_B;
-    const int c = 4 * half + 2 * h;
-    *reinterpret_cast<uint4*>(r + ((c ^ S::swz(row)) * 16)) = a;
-    *reinterpret_cast<uint4*>(r + (((c + 1) ^ S::swz(row)) * 16)) = b;
-}
-__device__ __forceinline__ void stage_put(char* st, int row, int h, int half, const f32x16& v, float) {
-    using S = OutStage<float>;
-    char* r = st + row * S::ROW_B;
-    const int c = 4 * h;        // one feature tile fills the line
-    (void)half;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<float4*>(r + (((c + q) ^ S::swz(row)) * 16)) =
-            make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
-}
-
 template <int NCT, int TT, typename OT>
 __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const TileRef& tr,
                                             const KernelArgs& a, uint4* smem) {
@@ -74,7 +42,7 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
     constexpr int TOK_WG = 4 * TOK_W;
     constexpr int SLAB_U4 = 2 * NCT * 64;          // one 32-feature tile of V_kept
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, h = lane >> 5;
     const int p = P->p;
     const int T = tr.n_tokens;
@@ -108,7 +76,7 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
     }
     __syncthreads();
 
-    bf16x8 bop[TT][2 * NCT];
+    bf16x8 aop[TT][2 * NCT];
 #pragma unroll
     for (int c = 0; c < NCT; ++c) {
         const uint32_t info = P->blk[2 * c + h];
@@ -154,8 +122,8 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
             bf16x8 f0, f1;
 #pragma unroll
             for (int i = 0; i < 8; ++i) { f0[i] = (__bf16)d[i]; f1[i] = (__bf16)d[8 + i]; }
-            bop[tt][2 * c] = f0;
-            bop[tt][2 * c + 1] = f1;
+            aop[tt][2 * c] = f0;
+            aop[tt][2 * c + 1] = f1;
         }
     }
     __syncthreads();          // record image is dead; the slabs reuse its space
@@ -163,40 +131,41 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
     // ---- sweep the feature tiles --------------------------------------------------------
     // LDS ring of NSTAGE basis slabs (one 32-feature tile each), filled by asynchronous
     // global->LDS transfers issued NSTAGE-1 tiles ahead.
-    constexpr int NSTAGE = 2;
+    constexpr int NSTAGE = kDecStages;
     constexpr int D = NSTAGE - 1;
     constexpr int NV = SLAB_U4 / kThreads;
     static_assert(SLAB_U4 % kThreads == 0, "whole transfers");
-    const uint4* vg = P->v_dec;
-    const int n_ft = p / 32;
+    const uint4* vg = uniform_ptr(P->v_dec);
+    const int n_ft = p / 32;                                   // even: p is a multiple of 64
     const uint32_t lds_ring = lds_offset(smem);
     auto issue = [&](int ft, int stage) {
-        const uint4* vsrc = vg + (size_t)ft * SLAB_U4 + wave * 64 + lane;
+        const uint4* vsrc = vg + (size_t)ft * SLAB_U4;
 #pragma unroll
         for (int i = 0; i < NV; ++i)
-            dma16_async(vsrc + i * kThreads,
+            dma16_async(vsrc + i * kThreads, (uint32_t)tid * 16u,
                         __builtin_amdgcn_readfirstlane(lds_ring + (stage * SLAB_U4 + i * kThreads + wave * 64) * 16));
     };
 
-    using OS = OutStage<OT>;
-    // store instruction k of a step covers rows k*RPI .. of this wave's 64 tokens; lane -> (row, column)
-    constexpr int NS = TOK_W / OS::RPI;                        // store instructions per PAIR of steps (never predicated off)
-    char* orow[NS];
-    int srow[NS];
-#pragma unroll
-    for (int k = 0; k < NS; ++k) {
-        srow[k] = k * OS::RPI + lane / OS::COLS;
-        int t = tok_tile0 + wave * TOK_W + srow[k];
-        t = t < T ? t : T - 1;                                 // tail: same bytes, same place as the last token
-        orow[k] = reinterpret_cast<char*>(reinterpret_cast<OT*>(const_cast<void*>(a.x)) + (tr.x_row0 + t) * a.ld_x) +
-                  (lane % OS::COLS) * 16;
-    }
+    // Output addressing.  Accumulator register i of token tile tt holds row tt*32 + 8*(i/4) + 4*h + i%4
+    // of this wave's tokens; the lane's two features of a pair of tiles are adjacent in memory.
+    // Rows past the end of the tensor are redirected to the last token's row (they hold its values).
+    constexpr int NST = 16 * TT;                               // stores per pair of feature tiles, never predicated off
+    const uint32_t ldb = (uint32_t)a.ld_x * (uint32_t)sizeof(OT);
+    const int n_valid = min(TOK_WG, T - tok_tile0);
+    const bool full = n_valid == TOK_WG;
+    char* obase = reinterpret_cast<char*>(const_cast<void*>(a.x)) + (size_t)(tr.x_row0 + tok_tile0) * (size_t)a.ld_x * sizeof(OT);
+    const uint32_t lane_row = (uint32_t)(wave * TOK_W + 4 * h);
+    const uint32_t lane_col = (uint32_t)(2 * l32 * (int)sizeof(OT));
+    const uint32_t lane_off = lane_row * ldb + lane_col;
+    auto put = [&](char* dst, float even, float odd) {
+        if constexpr (sizeof(OT) == 2) *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(even, odd);
+        else *reinterpret_cast<float2*>(dst) = make_float2(even, odd);
+    };
+
     // mu sits in LDS behind the ring: a global load inside the loop would make the compiler
     // wait for everything in flight, the asynchronous transfers included
     float* mu_lds = reinterpret_cast<float*>(smem + NSTAGE * SLAB_U4);
     for (int i = tid; i < p; i += kThreads) mu_lds[i] = P->mu[i];
-    const float* mu = mu_lds + 16 * h;
-    char* ostage = reinterpret_cast<char*>(mu_lds + p) + wave * (TOK_W * OS::ROW_B);       // this wave's transpose tile
 
 #pragma unroll
     for (int u = 0; u < D; ++u)
@@ -204,57 +173,75 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
     wait_vmem_times<NV>(min(D - 1, n_ft - 1));
     __syncthreads();
 
-    auto tile_step = [&](int ft, int stage) {
-        if (ft + D < n_ft) issue(ft + D, (stage + D) % NSTAGE);
-        f32x16 acc[TT];
-        {
-            f32x16 m;
+    for (int f0 = 0; f0 < n_ft; f0 += 2) {
+        f32x16 acc[2][TT];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = *reinterpret_cast<const float4*>(mu + ft * 32 + 4 * q);
-                m[4 * q] = v.x; m[4 * q + 1] = v.y; m[4 * q + 2] = v.z; m[4 * q + 3] = v.w;
+        for (int e = 0; e < 2; ++e) {
+            const int ft = f0 + e;
+            const int stage = NSTAGE == 2 ? e : ft % NSTAGE;
+            const bool more = ft + D < n_ft;
+            if (more) issue(ft + D, NSTAGE == 2 ? 1 - e : (ft + D) % NSTAGE);
+            {
+                const float2 m2 = *reinterpret_cast<const float2*>(mu_lds + f0 * 32 + 2 * l32);
+                const float m = e ? m2.y : m2.x;
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[e][tt][i] = m;
             }
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) acc[tt] = m;
-        }
-        constexpr int NSTEP = 2 * NCT;
-        const uint4* abase = smem + stage * SLAB_U4 + lane;
-        uint4 af[3];
-        af[0] = abase[0];
-        af[1] = abase[64];
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int ks = 0; ks < NSTEP; ++ks) {
-            if (ks + 2 < NSTEP) af[(ks + 2) % 3] = abase[(ks + 2) * 64];
-            const bf16x8 av = as_bf16x8_d(af[ks % 3]);
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
-                acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bop[tt][ks], acc[tt], 0, 0, 0);
+            constexpr int NSTEP = 2 * NCT;
+            const uint4* bbase = smem + stage * SLAB_U4 + lane;
+            uint4 bf[3];
+            bf[0] = bbase[0];
+            bf[1] = bbase[64];
             __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < NSTEP; ++ks) {
+                if (ks + 2 < NSTEP) bf[(ks + 2) % 3] = bbase[(ks + 2) * 64];
+                const bf16x8 bv = as_bf16x8_d(bf[ks % 3]);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    acc[e][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[tt][ks], bv, acc[e][tt], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (e == 1) {
+                char* ob = obase + (size_t)(f0 / 2) * (64 * sizeof(OT));
+                // (lane_off and last_row pass through an empty asm so that the 32 offsets are recomputed
+                // here -- one add each -- instead of being hoisted out of the sweep into registers the
+                // accumulators need)
+                if (full) {
+                    uint32_t lo = lane_off;
+                    asm volatile("" : "+v"(lo));
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            put(ob + (lo + (uint32_t)(tt * 32 + 8 * (i / 4) + i % 4) * ldb), acc[0][tt][i], acc[1][tt][i]);
+                } else {
+                    uint32_t last_row = (uint32_t)(n_valid - 1);
+                    asm volatile("" : "+v"(last_row));
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const uint32_t row = min(lane_row + (uint32_t)(tt * 32 + 8 * (i / 4) + i % 4), last_row);
+                            put(ob + (row * ldb + lane_col), acc[0][tt][i], acc[1][tt][i]);
+                        }
+                }
+            }
+            // The slab of the next step must have landed before the barrier publishes it.  Memory
+            // operations complete in issue order, so it is enough that no more operations are in
+            // flight than were issued after that slab's transfers: the transfers of the D-1 later
+            // slabs and the stores of the odd steps among the last D.  Near the end of the sweep
+            // fewer transfers are issued, so everything is waited for.
+            constexpr int kYoungerEven = (D - 1) * NV + (D / 2) * NST;
+            constexpr int kYoungerOdd = (D - 1) * NV + ((D + 1) / 2) * NST;
+            if (!more) wait_vmem<0>();
+            else if (e == 0) wait_vmem<(kYoungerEven < 63 ? kYoungerEven : 63)>();
+            else wait_vmem<(kYoungerOdd < 63 ? kYoungerOdd : 63)>();
+            __syncthreads();
         }
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) stage_put(ostage, tt * 32 + l32, h, ft % OS::FT_PER_ROW, acc[tt], OT());
-        // the slab of the next step (issued at the top of this one) must have landed; everything
-        // older -- the previous stores included -- is then complete as well (issue-order completion)
-        wait_vmem<0>();
-        __syncthreads();
-        if (ft % OS::FT_PER_ROW == OS::FT_PER_ROW - 1) {
-            // the 128-byte rows are complete: read them back row-contiguous (the
-            // barrier also orders this wave's LDS writes before these reads) and store whole lines
-            uint4 o[NS];
-#pragma unroll
-            for (int k = 0; k < NS; ++k)
-                o[k] = *reinterpret_cast<const uint4*>(ostage + srow[k] * OS::ROW_B + (((lane % OS::COLS) ^ OS::swz(srow[k])) * 16));
-#pragma unroll
-            for (int k = 0; k < NS; ++k) *reinterpret_cast<uint4*>(orow[k] + (size_t)(ft / OS::FT_PER_ROW) * OS::ROW_B) = o[k];
-        }
-    };
-    for (int f0 = 0; f0 < n_ft; f0 += NSTAGE) {
-#pragma unroll
-        for (int u = 0; u < NSTAGE; ++u)
-            if (f0 + u < n_ft) tile_step(f0 + u, u);
     }
-    __syncthreads();
 }
 
 // Two kernels, as for encode: narrow plans (two token tiles per wave, up to 320 padded
@@ -329,7 +316,7 @@ hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int gr
 int decode_lds_bytes(int nct, int tt, int rec_dwords, int p, kvtc_dtype dtype) {
     const int tok_wg = 4 * 32 * tt;
     const int rec_b = tok_wg * (rec_dwords + 1) * 4;
-    const int slab_b = 2 * 2 * nct * 1024 + p * 4 + tok_wg * 128;
+    const int slab_b = kDecStages * 2 * nct * 1024 + p * 4;
     (void)dtype;
     return rec_b > slab_b ? rec_b : slab_b;
 }

@@ -24,7 +24,7 @@ struct PlanDev {
     int32_t pad_;
     int32_t enc_wide, dec_wide;             // 0: served by the two-waves-per-SIMD kernel, 1: by the 512-register one
     const uint4* v_enc;    // [p/16][32*ntp/32][64] MFMA A fragments of V_kept^T (encode)
-    const uint4* v_dec;    // [p/32][2*nct][64]     MFMA A fragments of V_kept   (decode)
+    const uint4* v_dec;    // [p/32][2*nct][64]     MFMA B fragments of V_kept^T (decode); tiles 2k, 2k+1 = even, odd features of span k
     const float* negc;     // [32*ntp]  -(mu^T V_kept), zero in the padding
     const float* mu;       // [p]
     const uint32_t* blk;   // [64] per 16-coordinate block: bits | group << 8 | halfword offset << 16; 0 = padding
@@ -165,6 +165,21 @@ __device__ __forceinline__ uint32_t lds_offset(const void* p) {
 __device__ __forceinline__ void dma16_async(const void* gsrc, uint32_t lds_byte_addr) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :: "v"(gsrc), "s"(lds_byte_addr) : "memory");
+}
+
+// A pointer whose value is the same in every lane, moved into scalar registers.
+template <typename T> __device__ __forceinline__ const T* uniform_ptr(const T* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
+}
+
+// The same with a wave-uniform base (scalar registers) plus a 32-bit per-lane byte offset: the
+// per-transfer address arithmetic stays on the scalar unit and costs no vector registers.
+__device__ __forceinline__ void dma16_async(const void* base_uniform, uint32_t lane_byte_off, uint32_t lds_byte_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(lane_byte_off), "s"(base_uniform), "s"(lds_byte_addr) : "memory");
 }
 
 // s_waitcnt vmcnt(N) only (N <= 63): the N most recent vector-memory operations may stay in flight.
