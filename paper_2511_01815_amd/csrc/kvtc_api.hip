@@ -17,7 +17,9 @@ namespace kvtc {
 hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream);
 hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream);
 int encode_lds_bytes(int ntw, int wc, int n_groups, int rec_dwords, kvtc_dtype dtype);
-int decode_lds_bytes(int nct, int tt, int rec_dwords, int p, kvtc_dtype dtype);
+int decode_rec_bytes(int tt, int rec_dwords);
+int decode_ring_bytes(int nct);
+int decode_stage_u4(int nct);
 }  // namespace kvtc
 
 using namespace kvtc;
@@ -32,7 +34,8 @@ struct kvtc_plan {
 struct kvtc_batch {
     PlanDev* plans_dev;
     int n_plans;
-    int enc_lds[2][2], dec_lds[2][2];   // max over the plans of each kernel flavour (narrow, wide) and element dtype; -1: none
+    int enc_lds[2][2];                  // max over the plans of each kernel flavour (narrow, wide) and element dtype; -1: none
+    int dec_rec[2], dec_ring[2];        // decode, per kernel flavour: max record image, max basis ring + mu; -1: none
     int max_p;
     std::vector<int32_t> rec_dwords;
     uint32_t* rec_dwords_dev;
@@ -112,6 +115,16 @@ __global__ void __launch_bounds__(256) offsets_kernel(const uint32_t* rec_dwords
     if (tid == 0) offsets[n_jobs] = carry;
 }
 
+// Decode LDS layout for one launch: record image and basis ring side by side when both fit (narrow
+// kernel: within half a compute unit's LDS, so that two workgroups stay resident), which lets each
+// tile's records be fetched during the previous tile's sweep; otherwise they share the space.
+struct DecLayout { uint32_t ring_off; size_t lds_bytes; };
+DecLayout decode_layout(int rec_b, int ring_b, int wide) {
+    const int budget = (wide ? kLdsBudget : kLdsBudget / 2) - kJobTableBytes - 64;
+    if (rec_b + ring_b <= budget) return {(uint32_t)rec_b, (size_t)kJobTableBytes + 64 + rec_b + ring_b};
+    return {0u, (size_t)kJobTableBytes + 64 + (rec_b > ring_b ? rec_b : ring_b)};
+}
+
 }  // namespace
 
 extern "C" {
@@ -165,6 +178,8 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     d.r = r;
     d.n_groups = n_groups;
     d.n_blocks = r / 16;
+    for (int g = 0; g < n_groups; ++g)
+        if (groups_host[g].bits > d.code_bits_max) d.code_bits_max = groups_host[g].bits;
     const long total_bits = 32L * n_groups + payload_bits;
     d.rec_dwords = (int)((total_bits + 31) / 32);
     const int nt = (r + 31) / 32;
@@ -189,18 +204,20 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     {
         d.enc_lds[KVTC_BF16] = encode_lds_bytes(d.enc_ntw, d.enc_wc, n_groups, d.rec_dwords, KVTC_BF16);
         d.enc_lds[KVTC_F32] = encode_lds_bytes(d.enc_ntw, d.enc_wc, n_groups, d.rec_dwords, KVTC_F32);
-        d.dec_lds[KVTC_BF16] = decode_lds_bytes(d.dec_nct, d.dec_tt, d.rec_dwords, p, KVTC_BF16);
-        d.dec_lds[KVTC_F32] = decode_lds_bytes(d.dec_nct, d.dec_tt, d.rec_dwords, p, KVTC_F32);
+        d.dec_rec_lds = decode_rec_bytes(d.dec_tt, d.rec_dwords);
+        d.dec_ring_lds = decode_ring_bytes(d.dec_nct);
     }
     const int lds_cap = kLdsBudget - kJobTableBytes - 64;
-    if (d.enc_lds[0] > lds_cap || d.enc_lds[1] > lds_cap || d.dec_lds[0] > lds_cap || d.dec_lds[1] > lds_cap)
+    const int dec_need = d.dec_rec_lds > d.dec_ring_lds ? d.dec_rec_lds : d.dec_ring_lds;
+    if (d.enc_lds[0] > lds_cap || d.enc_lds[1] > lds_cap || dec_need > lds_cap)
         return fail(KVTC_E_UNSUPPORTED,
                     "kvtc_plan_create: record of %d bytes with r=%d needs %d/%d/%d bytes of LDS, %d available",
-                    d.rec_dwords * 4, r, d.enc_lds[0], d.enc_lds[1], d.dec_lds[0], lds_cap);
+                    d.rec_dwords * 4, r, d.enc_lds[0], d.enc_lds[1], dec_need, lds_cap);
 
     // ---- host images ---------------------------------------------------------------
     const size_t n_venc = (size_t)(p / 16) * ntp * 64 * 8;      // bf16 elements
-    const size_t n_vdec = (size_t)(p / 32) * 2 * d.dec_nct * 64 * 8;
+    const int stage_u4 = decode_stage_u4(d.dec_nct);              // fragments of a 32-feature tile, then its mu entries
+    const size_t n_vdec = (size_t)(p / 32) * stage_u4 * 8;
     std::vector<uint16_t> venc, vdec;
     std::vector<float> negc, mu;
     std::vector<uint32_t> blk(64, 0u), grp(n_groups, 0u);
@@ -227,10 +244,15 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
                 // tiles 2k and 2k+1 hold the even and the odd features of a 64-feature span
                 const int f = 64 * (ft >> 1) + 2 * (lane & 31) + (ft & 1);
                 const int j0 = 32 * (ks >> 1) + 16 * (lane >> 5) + 8 * (ks & 1);
-                uint16_t* dst = &vdec[((((size_t)ft * 2 * d.dec_nct) + ks) * 64 + lane) * 8];
+                uint16_t* dst = &vdec[(((size_t)ft * stage_u4) + (size_t)ks * 64 + lane) * 8];
                 for (int e = 0; e < 8; ++e)
                     if (j0 + e < r) dst[e] = v_kept_host[(size_t)f * r + j0 + e];
             }
+    for (int ft = 0; ft < p / 32; ++ft) {
+        float m[32];
+        for (int l = 0; l < 32; ++l) m[l] = mu_host[64 * (ft >> 1) + 2 * l + (ft & 1)];      // the lane order of the tile
+        memcpy(&vdec[((size_t)ft * stage_u4 + (size_t)2 * d.dec_nct * 64) * 8], m, sizeof(m));
+    }
     for (int j = 0; j < r; ++j) {
         double c = 0.0;
         for (int f = 0; f < p; ++f) c += (double)mu_host[f] * (double)bf16_bits_to_float(v_kept_host[(size_t)f * r + j]);
@@ -377,7 +399,9 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
     const int64_t tiles = (n_tokens + plan->h.dec_tok_wg - 1) / plan->h.dec_tok_wg;
     const int slots = cu_count() * (plan->h.dec_wide ? 1 : 2);
     const int grid = (int)(tiles < slots ? tiles : slots);
-    hipError_t e = launch_decode(a, dtype, plan->h.dec_wide, grid, (size_t)kJobTableBytes + 64 + plan->h.dec_lds[dtype], static_cast<hipStream_t>(stream));
+    const DecLayout lay = decode_layout(plan->h.dec_rec_lds, plan->h.dec_ring_lds, plan->h.dec_wide);
+    a.dec_ring_off = lay.ring_off;
+    hipError_t e = launch_decode(a, dtype, plan->h.dec_wide, grid, lay.lds_bytes, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }
@@ -392,7 +416,8 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
     b->rec_dwords_dev = nullptr;
     b->n_plans = n_plans;
     for (int f = 0; f < 2; ++f)
-        for (int dt = 0; dt < 2; ++dt) b->enc_lds[f][dt] = b->dec_lds[f][dt] = -1;
+        for (int dt = 0; dt < 2; ++dt) b->enc_lds[f][dt] = -1;
+    b->dec_rec[0] = b->dec_rec[1] = b->dec_ring[0] = b->dec_ring[1] = -1;
     b->max_p = 0;
     for (int i = 0; i < n_plans; ++i) {
         if (!plans[i]) {
@@ -404,8 +429,8 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
         const PlanDev& ph = plans[i]->h;
         for (int dt = 0; dt < 2; ++dt)
             if (ph.enc_lds[dt] > b->enc_lds[ph.enc_wide][dt]) b->enc_lds[ph.enc_wide][dt] = ph.enc_lds[dt];
-        for (int dt = 0; dt < 2; ++dt)
-            if (ph.dec_lds[dt] > b->dec_lds[ph.dec_wide][dt]) b->dec_lds[ph.dec_wide][dt] = ph.dec_lds[dt];
+        if (ph.dec_rec_lds > b->dec_rec[ph.dec_wide]) b->dec_rec[ph.dec_wide] = ph.dec_rec_lds;
+        if (ph.dec_ring_lds > b->dec_ring[ph.dec_wide]) b->dec_ring[ph.dec_wide] = ph.dec_ring_lds;
         if (ph.p > b->max_p) b->max_p = ph.p;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -513,9 +538,10 @@ kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.status = status_dev;
     if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_decode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
     for (int wide = 0; wide < 2; ++wide) {
-        if (batch->dec_lds[wide][dtype] < 0) continue;
-        hipError_t e = launch_decode(a, dtype, wide, cu_count() * (wide ? 1 : 2),
-                                     (size_t)kJobTableBytes + 64 + batch->dec_lds[wide][dtype], static_cast<hipStream_t>(stream));
+        if (batch->dec_rec[wide] < 0) continue;
+        const DecLayout lay = decode_layout(batch->dec_rec[wide], batch->dec_ring[wide], wide);
+        a.dec_ring_off = lay.ring_off;
+        hipError_t e = launch_decode(a, dtype, wide, cu_count() * (wide ? 1 : 2), lay.lds_bytes, static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode_batch: launch failed: %s", hipGetErrorString(e));
     }
     return KVTC_OK;

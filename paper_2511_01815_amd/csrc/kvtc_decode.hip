@@ -15,6 +15,7 @@
 // dword stores reach the same 5.7 TB/s as 16-byte stores of whole lines, while pieces of
 // 32 bytes per row reach 1.6 TB/s).
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include "kvtc_dev.h"
 #include "kvtc_numeric.h"
 
@@ -23,9 +24,14 @@ namespace kvtc {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kDecStages = 2;          // basis slabs in the LDS ring
-
 __device__ __forceinline__ bf16x8 as_bf16x8_d(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Work-area layout in LDS (behind the job table): [block table of the tile's plan, 256 B][record
+// image][basis ring].  The ring has two stages; a stage is one 32-feature slab of B fragments
+// followed by that tile's 32 entries of mu (kMuU4 * 16 bytes with padding).
+constexpr int kDecStages = 2;
+constexpr int kMuU4 = 16;
+constexpr int kAuxBytes = 256;
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -35,210 +41,239 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// Records of one workgroup tile (and the block table of its plan), global -> LDS, asynchronously
+// and without register staging: one dword per lane, 64 consecutive LDS dwords per instruction,
+// each fetched from wherever the padded row layout wants it (row stride rd + 1 dwords keeps the
+// unpacking loads of 32 lanes, one row each, on different banks).  Rows past the end of the tensor
+// replicate the last token's record, so every lane decodes something valid and the tail rows can
+// be stored unpredicated to the last token's place; the pad dword repeats the row's last dword
+// (never decoded).  Returns the number of transfers this wave issued; the caller owns the wait
+// (vmcnt) and the barrier that publishes the image.
+__device__ __forceinline__ int issue_records(const KernelArgs& a, const TileRef& t, const PlanDec& P, uint32_t lds_work) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rd = P.rec_dwords, tok_wg = P.dec_tok_wg;
+    const int tok0 = t.tile * tok_wg;
+    const uint32_t last_row = (uint32_t)(min(tok_wg, t.n_tokens - tok0) - 1);
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(a.stream_buf) + t.offset) + (size_t)tok0 * rd;
+    const uint32_t rstride = (uint32_t)rd + 1u;
+    const uint32_t total = (uint32_t)tok_wg * rstride;
+    const uint32_t magic = 0xffffffffu / rstride + 1u;
+    int n = 0;
+    if (wave == 0) {
+        dma4_async(P.blk, (uint32_t)lane * 4u, lds_work);
+        ++n;
+    }
+    for (uint32_t l0 = (uint32_t)wave * 64u; l0 < total; l0 += kThreads) {
+        const uint32_t l = l0 + (uint32_t)lane;
+        if (l < total) {
+            const uint32_t row = __umulhi(l, magic);
+            const uint32_t w = l - row * rstride;
+            const uint32_t off = (min(row, last_row) * (uint32_t)rd + min(w, (uint32_t)rd - 1u)) * 4u;
+            dma4_async(src, off, lds_work + kAuxBytes + l0 * 4u);
+        }
+        ++n;
+    }
+    return n;
+}
+
+// One workgroup tile.  The work area holds the tile's block table and record image, landed and
+// published.  With `prefetch` the ring does not overlap them: the first basis slab is requested
+// before unpacking, and the records of the workgroup's next tile (if any) are requested during
+// the first step of the feature sweep.
 template <int NCT, int TT, typename OT>
-__device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const TileRef& tr,
-                                            const KernelArgs& a, uint4* smem) {
+__device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr, const KernelArgs& a, uint4* work, uint4* ring,
+                                            bool prefetch, bool has_next, const TileRef& next, const PlanDec& Pn) {
     constexpr int TOK_W = 32 * TT;
     constexpr int TOK_WG = 4 * TOK_W;
     constexpr int SLAB_U4 = 2 * NCT * 64;          // one 32-feature tile of V_kept
+    constexpr int STAGE_U4 = SLAB_U4 + kMuU4;
+    constexpr int NV = SLAB_U4 / kThreads;
+    static_assert(SLAB_U4 % kThreads == 0, "whole transfers");
+    static_assert(kDecStages == 2, "the wait counts below are written out for a ring of two slabs");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, h = lane >> 5;
-    const int p = P->p;
+    const int p = P.p;
     const int T = tr.n_tokens;
     const int tok_tile0 = tr.tile * TOK_WG;
-    const int rd = P->rec_dwords;
+    const int rd = P.rec_dwords;
     const int rstride = rd + 1;
-
-    // ---- records -> LDS (coalesced), then each lane unpacks its blocks ---------------
-    uint32_t* rec = reinterpret_cast<uint32_t*>(smem);
-    {
-        const int n_valid = min(TOK_WG, T - tok_tile0);
-        const uint32_t* in = reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(a.stream_buf) + tr.offset) +
-                             (size_t)tok_tile0 * rd;
-        const uint32_t magic = 0xffffffffu / (uint32_t)rd + 1u;
-        const int total = n_valid * rd;
-        for (int i = tid; i < total; i += kThreads) {
-            const uint32_t t = __umulhi((uint32_t)i, magic);
-            rec[t * rstride + ((uint32_t)i - t * rd)] = in[i];
-        }
-        // pad dwords: defined contents.  Rows past the end of the tensor replicate the last token's
-        // record, so every lane decodes something valid and the tail lanes store the same bytes to
-        // the same place as the last token's lane: no store is ever predicated off, which keeps the
-        // number of memory operations per step fixed (the explicit vmcnt waits count on it).
-        for (int i = tid; i < TOK_WG; i += kThreads) rec[i * rstride + rd] = 0u;
-        const uint32_t* last = in + (size_t)(n_valid - 1) * rd;
-        for (int i = total + tid; i < TOK_WG * rd; i += kThreads) {
-            const uint32_t t = __umulhi((uint32_t)i, magic);
-            const uint32_t w = (uint32_t)i - t * rd;
-            rec[t * rstride + w] = last[w];
-        }
-    }
-    __syncthreads();
-
-    bf16x8 aop[TT][2 * NCT];
-#pragma unroll
-    for (int c = 0; c < NCT; ++c) {
-        const uint32_t info = P->blk[2 * c + h];
-        const uint32_t bits = info & 0xffu;
-        const uint32_t g = (info >> 8) & 0xffu;
-        const uint32_t pos0 = (info >> 16) * 16u;
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-            float d[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) d[i] = 0.0f;
-            if (bits != 0u) {
-                const uint32_t* row = rec + (wave * TOK_W + tt * 32 + l32) * rstride;
-                const uint32_t hdr = row[g];
-                const float shift = f16_bits_to_f32((uint16_t)(hdr & 0xffffu));
-                const float scale = f16_bits_to_f32((uint16_t)(hdr >> 16));
-                if (bits <= 8u) {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const uint32_t pos = pos0 + 4u * k * bits;
-                        const uint32_t dw = pos >> 5;
-                        const uint32_t w = __builtin_amdgcn_alignbit(row[dw + 1], row[dw], pos & 31u);
-#pragma unroll
-                        for (int m = 0; m < 4; ++m) {
-                            const uint32_t code = __builtin_amdgcn_ubfe(w, m * bits, bits);
-                            d[4 * k + m] = __fmaf_rn((float)code, scale, shift);
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        const uint32_t pos = pos0 + 2u * k * bits;
-                        const uint32_t dw = pos >> 5;
-                        const uint32_t w = __builtin_amdgcn_alignbit(row[dw + 1], row[dw], pos & 31u);
-#pragma unroll
-                        for (int m = 0; m < 2; ++m) {
-                            const uint32_t code = __builtin_amdgcn_ubfe(w, m * bits, bits);
-                            d[2 * k + m] = __fmaf_rn((float)code, scale, shift);
-                        }
-                    }
-                }
-            }
-            bf16x8 f0, f1;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { f0[i] = (__bf16)d[i]; f1[i] = (__bf16)d[8 + i]; }
-            aop[tt][2 * c] = f0;
-            aop[tt][2 * c + 1] = f1;
-        }
-    }
-    __syncthreads();          // record image is dead; the slabs reuse its space
-
-    // ---- sweep the feature tiles --------------------------------------------------------
-    // LDS ring of NSTAGE basis slabs (one 32-feature tile each), filled by asynchronous
-    // global->LDS transfers issued NSTAGE-1 tiles ahead.
-    constexpr int NSTAGE = kDecStages;
-    constexpr int D = NSTAGE - 1;
-    constexpr int NV = SLAB_U4 / kThreads;
-    static_assert(SLAB_U4 % kThreads == 0, "whole transfers");
-    const uint4* vg = uniform_ptr(P->v_dec);
     const int n_ft = p / 32;                                   // even: p is a multiple of 64
-    const uint32_t lds_ring = lds_offset(smem);
-    auto issue = [&](int ft, int stage) {
-        const uint4* vsrc = vg + (size_t)ft * SLAB_U4;
+
+    // basis slab of feature tile ft -> ring stage; wave 0 also moves the tile's mu entries
+    const uint4* vg = P.v_dec;
+    const uint32_t lds_ring = lds_offset(ring);
+    auto issue_slab = [&](int ft, int stage) {
+        const uint4* vsrc = vg + (size_t)ft * STAGE_U4;
+        const uint32_t dst = lds_ring + (uint32_t)(stage * STAGE_U4) * 16u;
 #pragma unroll
         for (int i = 0; i < NV; ++i)
-            dma16_async(vsrc + i * kThreads, (uint32_t)tid * 16u,
-                        __builtin_amdgcn_readfirstlane(lds_ring + (stage * SLAB_U4 + i * kThreads + wave * 64) * 16));
+            dma16_async(vsrc + i * kThreads, (uint32_t)tid * 16u, dst + (uint32_t)(i * kThreads + wave * 64) * 16u);
+        if (wave == 0 && lane < kMuU4) dma16_async(vsrc + SLAB_U4, (uint32_t)lane * 16u, dst + (uint32_t)SLAB_U4 * 16u);
     };
+    if (prefetch) issue_slab(0, 0);
 
+    // ---- each lane unpacks its blocks from the record image ------------------------------
+    // A lane owns one token (l32) and, per 32-coordinate tile, the 16-coordinate block of its half h.
+    const uint32_t* blk = reinterpret_cast<const uint32_t*>(work);
+    const uint32_t* rec = blk + kAuxBytes / 4;
+    bf16x8 aop[TT][2 * NCT];
+    // codes of up to 8 bits (all that calibration produces) come four to a 32-bit window, wider
+    // ones two; the choice is made once per plan
+    auto unpack = [&](auto narrow_tag) {
+        constexpr bool kNarrow = decltype(narrow_tag)::value;
+        constexpr int PER = kNarrow ? 4 : 2;                   // codes per window
+#pragma unroll
+        for (int c = 0; c < NCT; ++c) {
+            const uint32_t info = blk[2 * c + h];
+            const uint32_t bits = info & 0xffu;
+            const uint32_t g = (info >> 8) & 0xffu;
+            const uint32_t pos0 = (info >> 16) * 16u;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const uint32_t* row = rec + (wave * TOK_W + tt * 32 + l32) * rstride;
+                const uint32_t hdr = bits != 0u ? row[g] : 0u;      // a block without bits decodes to zeros
+                const float shift = f16_bits_to_f32((uint16_t)(hdr & 0xffffu));
+                const float scale = f16_bits_to_f32((uint16_t)(hdr >> 16));
+                uint32_t q[8];                                      // the block's 16 values as bf16 pairs
+#pragma unroll
+                for (int k = 0; k < 16 / PER; ++k) {
+                    const uint32_t pos = pos0 + (uint32_t)(PER * k) * bits;
+                    const uint32_t dw = pos >> 5;
+                    const uint32_t w = __builtin_amdgcn_alignbit(row[dw + 1], row[dw], pos & 31u);
+#pragma unroll
+                    for (int m = 0; m < PER; m += 2) {
+                        const float d0 = __fmaf_rn((float)__builtin_amdgcn_ubfe(w, m * bits, bits), scale, shift);
+                        const float d1 = __fmaf_rn((float)__builtin_amdgcn_ubfe(w, (m + 1) * bits, bits), scale, shift);
+                        q[(PER * k + m) / 2] = pack_bf16x2(d0, d1);
+                    }
+                }
+                // (through an empty asm: the conversions are done here, block by block, instead of all the
+                // fp32 values staying live until the end of the unpacking)
+                asm volatile("" : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]), "+v"(q[4]), "+v"(q[5]), "+v"(q[6]), "+v"(q[7]));
+                aop[tt][2 * c] = __builtin_bit_cast(bf16x8, make_uint4(q[0], q[1], q[2], q[3]));
+                aop[tt][2 * c + 1] = __builtin_bit_cast(bf16x8, make_uint4(q[4], q[5], q[6], q[7]));
+            }
+        }
+    };
+    if (P.code_bits_max <= 8) unpack(std::true_type()); else unpack(std::false_type());
+    if (!prefetch) {
+        __syncthreads();          // record image is dead; the ring reuses its space
+        issue_slab(0, 0);
+    }
+    wait_vmem<0>();
+    __syncthreads();              // slab 0 is published (and, with prefetch, the record image is dead)
+
+    // ---- sweep the feature tiles --------------------------------------------------------
     // Output addressing.  Accumulator register i of token tile tt holds row tt*32 + 8*(i/4) + 4*h + i%4
     // of this wave's tokens; the lane's two features of a pair of tiles are adjacent in memory.
-    // Rows past the end of the tensor are redirected to the last token's row (they hold its values).
-    constexpr int NST = 16 * TT;                               // stores per pair of feature tiles, never predicated off
+    // Rows past the end of the tensor are redirected to the last token's row (they hold its values),
+    // so no store is ever predicated off and the number of memory operations per step is fixed.
+    constexpr int NST = 16 * TT;                               // stores per pair of feature tiles
     const uint32_t ldb = (uint32_t)a.ld_x * (uint32_t)sizeof(OT);
     const int n_valid = min(TOK_WG, T - tok_tile0);
-    const bool full = n_valid == TOK_WG;
     char* obase = reinterpret_cast<char*>(const_cast<void*>(a.x)) + (size_t)(tr.x_row0 + tok_tile0) * (size_t)a.ld_x * sizeof(OT);
     const uint32_t lane_row = (uint32_t)(wave * TOK_W + 4 * h);
     const uint32_t lane_col = (uint32_t)(2 * l32 * (int)sizeof(OT));
-    const uint32_t lane_off = lane_row * ldb + lane_col;
-    auto put = [&](char* dst, float even, float odd) {
-        if constexpr (sizeof(OT) == 2) *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(even, odd);
-        else *reinterpret_cast<float2*>(dst) = make_float2(even, odd);
+    const uint32_t last_row = (uint32_t)(n_valid - 1);
+
+    // One 32-feature tile: the accumulators start from mu and sweep the coordinates.
+    auto tile_step = [&](int stage, f32x16 (&acc)[TT]) {
+        const uint4* bbase = ring + stage * STAGE_U4 + lane;
+        {
+            const float m = reinterpret_cast<const float*>(ring + stage * STAGE_U4 + SLAB_U4)[l32];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[tt][i] = m;
+        }
+        constexpr int NSTEP = 2 * NCT;
+        uint4 bf[3];
+        bf[0] = bbase[0];
+        bf[1] = bbase[64];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < NSTEP; ++ks) {
+            if (ks + 2 < NSTEP) bf[(ks + 2) % 3] = bbase[(ks + 2) * 64];
+            const bf16x8 bv = as_bf16x8_d(bf[ks % 3]);
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+                acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[tt][ks], bv, acc[tt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
-    // mu sits in LDS behind the ring: a global load inside the loop would make the compiler
-    // wait for everything in flight, the asynchronous transfers included
-    float* mu_lds = reinterpret_cast<float*>(smem + NSTAGE * SLAB_U4);
-    for (int i = tid; i < p; i += kThreads) mu_lds[i] = P->mu[i];
-
-#pragma unroll
-    for (int u = 0; u < D; ++u)
-        if (u < n_ft) issue(u, u);
-    wait_vmem_times<NV>(min(D - 1, n_ft - 1));
-    __syncthreads();
-
+    // Waits: the slab of the next step must have landed before the barrier publishes it.  Memory
+    // operations complete in issue order, so it is enough that no more operations are in flight
+    // than this wave issued after that slab's transfers (the next tile's records in the first
+    // step, the stores in odd steps).
     for (int f0 = 0; f0 < n_ft; f0 += 2) {
-        f32x16 acc[2][TT];
+        f32x16 acc0[TT], acc1[TT];
+        issue_slab(f0 + 1, 1);
+        int n_rec = 0;
+        if (f0 == 0 && has_next) n_rec = issue_records(a, next, Pn, lds_offset(work));
+        tile_step(0, acc0);
+        if (f0 == 0) wait_vmem_dyn(n_rec); else wait_vmem<0>();
+        __syncthreads();
+
+        const bool more = f0 + 2 < n_ft;
+        if (more) issue_slab(f0 + 2, 0);
+        tile_step(1, acc1);
+        {
+            char* ob = obase + (size_t)(f0 / 2) * (64 * sizeof(OT));
+            // (through an empty asm so that the 16*TT offsets are recomputed here -- three vector
+            // instructions each -- instead of being hoisted out of the sweep into registers the
+            // accumulators need)
+            uint32_t lrow = lane_row;
+            asm volatile("" : "+v"(lrow));
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int ft = f0 + e;
-            const int stage = NSTAGE == 2 ? e : ft % NSTAGE;
-            const bool more = ft + D < n_ft;
-            if (more) issue(ft + D, NSTAGE == 2 ? 1 - e : (ft + D) % NSTAGE);
-            {
-                const float2 m2 = *reinterpret_cast<const float2*>(mu_lds + f0 * 32 + 2 * l32);
-                const float m = e ? m2.y : m2.x;
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[e][tt][i] = m;
+            for (int k = 0; k < NST; ++k) {
+                const int tt = k / 16, i = k % 16;
+                const uint32_t row = min(lrow + (uint32_t)(tt * 32 + 8 * (i / 4) + i % 4), last_row);
+                char* dst = ob + (__umul24(row, ldb) + lane_col);              // row < 256, ldb <= 2^23
+                if constexpr (sizeof(OT) == 2) *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(acc0[tt][i], acc1[tt][i]);
+                else *reinterpret_cast<float2*>(dst) = make_float2(acc0[tt][i], acc1[tt][i]);
             }
-            constexpr int NSTEP = 2 * NCT;
-            const uint4* bbase = smem + stage * SLAB_U4 + lane;
-            uint4 bf[3];
-            bf[0] = bbase[0];
-            bf[1] = bbase[64];
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int ks = 0; ks < NSTEP; ++ks) {
-                if (ks + 2 < NSTEP) bf[(ks + 2) % 3] = bbase[(ks + 2) * 64];
-                const bf16x8 bv = as_bf16x8_d(bf[ks % 3]);
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    acc[e][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[tt][ks], bv, acc[e][tt], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            if (e == 1) {
-                char* ob = obase + (size_t)(f0 / 2) * (64 * sizeof(OT));
-                // (lane_off and last_row pass through an empty asm so that the 32 offsets are recomputed
-                // here -- one add each -- instead of being hoisted out of the sweep into registers the
-                // accumulators need)
-                if (full) {
-                    uint32_t lo = lane_off;
-                    asm volatile("" : "+v"(lo));
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i)
-                            put(ob + (lo + (uint32_t)(tt * 32 + 8 * (i / 4) + i % 4) * ldb), acc[0][tt][i], acc[1][tt][i]);
-                } else {
-                    uint32_t last_row = (uint32_t)(n_valid - 1);
-                    asm volatile("" : "+v"(last_row));
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const uint32_t row = min(lane_row + (uint32_t)(tt * 32 + 8 * (i / 4) + i % 4), last_row);
-                            put(ob + (row * ldb + lane_col), acc[0][tt][i], acc[1][tt][i]);
-                        }
-                }
-            }
-            // The slab of the next step must have landed before the barrier publishes it.  Memory
-            // operations complete in issue order, so it is enough that no more operations are in
-            // flight than were issued after that slab's transfers: the transfers of the D-1 later
-            // slabs and the stores of the odd steps among the last D.  Near the end of the sweep
-            // fewer transfers are issued, so everything is waited for.
-            constexpr int kYoungerEven = (D - 1) * NV + (D / 2) * NST;
-            constexpr int kYoungerOdd = (D - 1) * NV + ((D + 1) / 2) * NST;
-            if (!more) wait_vmem<0>();
-            else if (e == 0) wait_vmem<(kYoungerEven < 63 ? kYoungerEven : 63)>();
-            else wait_vmem<(kYoungerOdd < 63 ? kYoungerOdd : 63)>();
+        }
+        if (more) wait_vmem<NST>(); else wait_vmem<0>();
+        __syncthreads();
+    }
+}
+
+// The persistent tile loop shared by both kernels.  With a non-zero a.dec_ring_off the ring sits
+// behind the record image and each tile's records are fetched during the previous tile's sweep;
+// with offset 0 they share the space and the records are fetched at the tile's start.
+template <typename OT, int kWide, typename Dispatch>
+__device__ __forceinline__ void decode_loop(const KernelArgs& a, uint4* smem, Dispatch dispatch) {
+    uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
+    uint4* work = smem + kJobTableBytes / 16 + 1;
+    const uint32_t total = build_tile_table<false, kWide>(a, tile_start, reinterpret_cast<uint32_t*>(work));
+    uint32_t tile = blockIdx.x;
+    if (tile >= total) return;
+    const bool prefetch = a.dec_ring_off != 0u;
+    uint4* ring = work + a.dec_ring_off / 16u;
+    TileRef tr = find_tile(a, tile_start, tile);
+    PlanDec P = load_plan_dec(a.plans + tr.plan);
+    issue_records(a, tr, P, lds_offset(work));
+    wait_vmem<0>();
+    __syncthreads();
+    for (;;) {
+        const uint32_t next = tile + gridDim.x;
+        const bool has_next = next < total;
+        TileRef trn = tr;
+        PlanDec Pn = P;
+        if (has_next) {
+            trn = find_tile(a, tile_start, next);
+            Pn = load_plan_dec(a.plans + trn.plan);
+        }
+        dispatch(P.dec_tt * 100 + P.dec_nct, P, tr, work, ring, prefetch, has_next && prefetch, trn, Pn);
+        if (!has_next) break;
+        tile = next;
+        tr = trn;
+        P = Pn;
+        if (!prefetch) {
+            issue_records(a, tr, P, lds_offset(work));
+            wait_vmem<0>();
             __syncthreads();
         }
     }
@@ -246,43 +281,33 @@ __device__ __forceinline__ void decode_tile(const PlanDev* __restrict__ P, const
 
 // Two kernels, as for encode: narrow plans (two token tiles per wave, up to 320 padded
 // coordinates) run two workgroups per compute unit, wide ones get the whole register file.
+#define KVTC_DISPATCH_ARGS int key, const PlanDec& P, const TileRef& tr, uint4* work, uint4* ring, bool prefetch, bool has_next, \
+                           const TileRef& next, const PlanDec& Pn
+#define KVTC_CASE(TT, NCT) \
+    case (TT) * 100 + (NCT): decode_tile<NCT, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break;
 template <typename OT>
 __global__ void __launch_bounds__(kThreads, 2) kvtc_decode_kernel(const KernelArgs a) {
     extern __shared__ uint4 smem[];
-    uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
-    uint4* work = smem + kJobTableBytes / 16 + 1;
-    const uint32_t total = build_tile_table<false, 0>(a, tile_start, reinterpret_cast<uint32_t*>(work));
-    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
-        const TileRef tr = find_tile(a, tile_start, tile);
-        const PlanDev* P = a.plans + tr.plan;
-        const int key = __builtin_amdgcn_readfirstlane(P->dec_tt * 100 + P->dec_nct);
+    decode_loop<OT, 0>(a, smem, [&](KVTC_DISPATCH_ARGS) {
         switch (key) {
-#define KVTC_CASE(TT, NCT) case (TT) * 100 + (NCT): decode_tile<NCT, TT, OT>(P, tr, a, work); break;
             KVTC_CASE(2, 2) KVTC_CASE(2, 4) KVTC_CASE(2, 6) KVTC_CASE(2, 8) KVTC_CASE(2, 10)
-#undef KVTC_CASE
             default: break;
         }
-    }
+    });
 }
 
 template <typename OT>
 __global__ void __launch_bounds__(kThreads, 1) kvtc_decode_wide_kernel(const KernelArgs a) {
     extern __shared__ uint4 smem[];
-    uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
-    uint4* work = smem + kJobTableBytes / 16 + 1;
-    const uint32_t total = build_tile_table<false, 1>(a, tile_start, reinterpret_cast<uint32_t*>(work));
-    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
-        const TileRef tr = find_tile(a, tile_start, tile);
-        const PlanDev* P = a.plans + tr.plan;
-        const int key = __builtin_amdgcn_readfirstlane(P->dec_tt * 100 + P->dec_nct);
+    decode_loop<OT, 1>(a, smem, [&](KVTC_DISPATCH_ARGS) {
         switch (key) {
-#define KVTC_CASE(TT, NCT) case (TT) * 100 + (NCT): decode_tile<NCT, TT, OT>(P, tr, a, work); break;
             KVTC_CASE(1, 12) KVTC_CASE(1, 16) KVTC_CASE(1, 20) KVTC_CASE(1, 24) KVTC_CASE(1, 32)
-#undef KVTC_CASE
             default: break;
         }
-    }
+    });
 }
+#undef KVTC_CASE
+#undef KVTC_DISPATCH_ARGS
 
 template <typename K>
 static hipError_t set_lds_attr_d(K kernel) {
@@ -313,12 +338,13 @@ hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int gr
     return hipGetLastError();
 }
 
-int decode_lds_bytes(int nct, int tt, int rec_dwords, int p, kvtc_dtype dtype) {
+// Bytes of the block table + record image and of the basis ring of a decode variant (the host
+// lays them out: side by side when both fit, else sharing the space).
+int decode_rec_bytes(int tt, int rec_dwords) {
     const int tok_wg = 4 * 32 * tt;
-    const int rec_b = tok_wg * (rec_dwords + 1) * 4;
-    const int slab_b = kDecStages * 2 * nct * 1024 + p * 4;
-    (void)dtype;
-    return rec_b > slab_b ? rec_b : slab_b;
+    return kAuxBytes + (tok_wg * (rec_dwords + 1) * 4 + 255) / 256 * 256;      // whole 64-dword transfers
 }
+int decode_ring_bytes(int nct) { return kDecStages * (2 * nct * 64 + kMuU4) * 16; }
+int decode_stage_u4(int nct) { return 2 * nct * 64 + kMuU4; }
 
 }  // namespace kvtc

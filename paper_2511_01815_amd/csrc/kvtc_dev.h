@@ -2,6 +2,7 @@
 // decode kernels.  Internal to the library.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 #include "../../include/kvtc.h"
 
@@ -20,11 +21,12 @@ struct PlanDev {
     int32_t enc_ntw, enc_wc;                // encode variant: coefficient tiles per wave, waves across coefficients
     int32_t dec_nct, dec_tt;                // decode variant: coefficient tiles, token tiles per wave
     int32_t enc_tok_wg, dec_tok_wg;         // tokens per workgroup tile
-    int32_t enc_lds[2], dec_lds[2];         // dynamic LDS bytes needed (without the job table), per element dtype
-    int32_t pad_;
+    int32_t enc_lds[2];                     // encode: dynamic LDS bytes needed (without the job table), per element dtype
+    int32_t dec_rec_lds, dec_ring_lds;      // decode: bytes of the record image, of the basis ring + mu
+    int32_t code_bits_max;                  // widest code of the plan
     int32_t enc_wide, dec_wide;             // 0: served by the two-waves-per-SIMD kernel, 1: by the 512-register one
     const uint4* v_enc;    // [p/16][32*ntp/32][64] MFMA A fragments of V_kept^T (encode)
-    const uint4* v_dec;    // [p/32][2*nct][64]     MFMA B fragments of V_kept^T (decode); tiles 2k, 2k+1 = even, odd features of span k
+    const uint4* v_dec;    // [p/32][2*nct*64 + 16] MFMA B fragments of V_kept^T (decode), then the tile's 32 mu entries; tiles 2k, 2k+1 = even, odd features of span k
     const float* negc;     // [32*ntp]  -(mu^T V_kept), zero in the padding
     const float* mu;       // [p]
     const uint32_t* blk;   // [64] per 16-coordinate block: bits | group << 8 | halfword offset << 16; 0 = padding
@@ -43,6 +45,7 @@ struct KernelArgs {
     void* stream_buf;          // record stream (encode: output, decode: input)
     uint64_t cap;              // bytes available in stream_buf
     uint32_t* status;          // device, may be nullptr
+    uint32_t dec_ring_off;     // decode: byte offset of the basis ring in the work area; 0 = it shares the record image's space
 };
 
 struct TileRef {
@@ -117,6 +120,58 @@ __device__ inline uint32_t build_tile_table(const KernelArgs& a, uint32_t* tile_
     return total;
 }
 
+// A pointer whose value is the same in every lane, moved into scalar registers.
+template <typename T> __device__ __forceinline__ const T* uniform_ptr(const T* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
+}
+
+// Wave-uniform loads through the scalar unit (read-only data written before the launch: job
+// list, stream offsets, plan descriptors).  They count on lgkmcnt, not on vmcnt, so they neither
+// wait for nor disturb the vector-memory operations a kernel keeps in flight.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4 sload_x4(const void* p_uniform) {
+    u32x4 v;
+    asm volatile("s_load_dwordx4 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(uniform_ptr(reinterpret_cast<const char*>(p_uniform))) : "memory");
+    return v;
+}
+__device__ __forceinline__ u32x2 sload_x2(const void* p_uniform) {
+    u32x2 v;
+    asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(uniform_ptr(reinterpret_cast<const char*>(p_uniform))) : "memory");
+    return v;
+}
+template <typename T> __device__ __forceinline__ T* sload_ptr(const void* p_uniform) {
+    const u32x2 v = sload_x2(p_uniform);
+    return reinterpret_cast<T*>(((uint64_t)v[1] << 32) | v[0]);
+}
+
+// The fields of a plan descriptor the decode kernel uses, in scalar registers.
+struct PlanDec {
+    int32_t p, rec_dwords, dec_nct, dec_tt, dec_tok_wg, code_bits_max;
+    const uint4* v_dec;
+    const uint32_t* blk;
+};
+__device__ __forceinline__ PlanDec load_plan_dec(const PlanDev* P) {
+    static_assert(offsetof(PlanDev, p) == 0 && offsetof(PlanDev, rec_dwords) == 16 && offsetof(PlanDev, dec_nct) == 28 &&
+                  offsetof(PlanDev, dec_tt) == 32 && offsetof(PlanDev, dec_tok_wg) == 40, "descriptor layout");
+    const char* b = reinterpret_cast<const char*>(P);
+    static_assert(offsetof(PlanDev, code_bits_max) == 60, "descriptor layout");
+    const u32x4 q0 = sload_x4(b), q1 = sload_x4(b + 16), q2 = sload_x4(b + 32), q3 = sload_x4(b + 48);
+    PlanDec d;
+    d.p = (int32_t)q0[0];
+    d.rec_dwords = (int32_t)q1[0];
+    d.dec_nct = (int32_t)q1[3];
+    d.dec_tt = (int32_t)q2[0];
+    d.dec_tok_wg = (int32_t)q2[2];
+    d.code_bits_max = (int32_t)q3[3];
+    d.v_dec = sload_ptr<const uint4>(b + offsetof(PlanDev, v_dec));
+    d.blk = sload_ptr<const uint32_t>(b + offsetof(PlanDev, blk));
+    return d;
+}
+
 __device__ inline TileRef find_tile(const KernelArgs& a, const uint32_t* tile_start, uint32_t tile) {
     const int n_jobs = a.jobs ? a.n_jobs : 1;
     int lo = 0, hi = n_jobs;                 // invariant: tile_start[lo] <= tile < tile_start[hi]
@@ -125,13 +180,24 @@ __device__ inline TileRef find_tile(const KernelArgs& a, const uint32_t* tile_st
         if (tile_start[mid] <= tile) lo = mid; else hi = mid;
     }
     lo = __builtin_amdgcn_readfirstlane(lo);
-    const kvtc_job jb = a.jobs ? a.jobs[lo] : a.single;
+    static_assert(sizeof(kvtc_job) == 16 && offsetof(kvtc_job, n_tokens) == 4 && offsetof(kvtc_job, x_row0) == 8, "job layout");
     TileRef t;
     t.job = lo;
-    t.plan = __builtin_amdgcn_readfirstlane(jb.plan);
-    t.n_tokens = __builtin_amdgcn_readfirstlane(jb.n_tokens);
-    t.x_row0 = jb.x_row0;
-    t.offset = a.offsets ? a.offsets[lo] : 0ull;
+    if (a.jobs) {
+        const u32x4 jb = sload_x4(a.jobs + lo);
+        t.plan = (int32_t)jb[0];
+        t.n_tokens = (int32_t)jb[1];
+        t.x_row0 = (int64_t)(((uint64_t)jb[3] << 32) | jb[2]);
+    } else {
+        t.plan = a.single.plan;
+        t.n_tokens = a.single.n_tokens;
+        t.x_row0 = a.single.x_row0;
+    }
+    t.offset = 0ull;
+    if (a.offsets) {
+        const u32x2 o = sload_x2(a.offsets + lo);
+        t.offset = ((uint64_t)o[1] << 32) | o[0];
+    }
     t.tile = (int32_t)(tile - tile_start[lo]);
     t.tile = __builtin_amdgcn_readfirstlane(t.tile);
     return t;
@@ -167,19 +233,21 @@ __device__ __forceinline__ void dma16_async(const void* gsrc, uint32_t lds_byte_
                  :: "v"(gsrc), "s"(lds_byte_addr) : "memory");
 }
 
-// A pointer whose value is the same in every lane, moved into scalar registers.
-template <typename T> __device__ __forceinline__ const T* uniform_ptr(const T* p) {
-    const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
-}
-
 // The same with a wave-uniform base (scalar registers) plus a 32-bit per-lane byte offset: the
 // per-transfer address arithmetic stays on the scalar unit and costs no vector registers.
+// (Values the compiler cannot prove uniform would reach the "s" operands in vector registers, so
+// both go through readfirstlane, which folds away when they already are scalar.)
 __device__ __forceinline__ void dma16_async(const void* base_uniform, uint32_t lane_byte_off, uint32_t lds_byte_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(lane_byte_off), "s"(base_uniform), "s"(lds_byte_addr) : "memory");
+                 :: "v"(lane_byte_off), "s"(uniform_ptr(reinterpret_cast<const char*>(base_uniform))),
+                    "s"(__builtin_amdgcn_readfirstlane(lds_byte_addr)) : "memory");
+}
+
+// One dword per lane: lane i's dword lands at lds_byte_addr + 4 * i.
+__device__ __forceinline__ void dma4_async(const void* base_uniform, uint32_t lane_byte_off, uint32_t lds_byte_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :: "v"(lane_byte_off), "s"(uniform_ptr(reinterpret_cast<const char*>(base_uniform))),
+                    "s"(__builtin_amdgcn_readfirstlane(lds_byte_addr)) : "memory");
 }
 
 // s_waitcnt vmcnt(N) only (N <= 63): the N most recent vector-memory operations may stay in flight.
@@ -188,15 +256,14 @@ template <int N> __device__ __forceinline__ void wait_vmem() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 __device__ __forceinline__ void wait_vmem_all() { wait_vmem<0>(); }
-// s_waitcnt vmcnt(n) with a wave-uniform run-time n; n above 31 waits as for 31.
+// s_waitcnt vmcnt(n) with a wave-uniform run-time n; n above 63 waits as for 63.
 __device__ __forceinline__ void wait_vmem_dyn(int n) {
 #define KVTC_W(N) case N: wait_vmem<N>(); break;
-    switch (n < 0 ? 0 : (n > 31 ? 31 : n)) {
-        KVTC_W(0) KVTC_W(1) KVTC_W(2) KVTC_W(3) KVTC_W(4) KVTC_W(5) KVTC_W(6) KVTC_W(7)
-        KVTC_W(8) KVTC_W(9) KVTC_W(10) KVTC_W(11) KVTC_W(12) KVTC_W(13) KVTC_W(14) KVTC_W(15)
-        KVTC_W(16) KVTC_W(17) KVTC_W(18) KVTC_W(19) KVTC_W(20) KVTC_W(21) KVTC_W(22) KVTC_W(23)
-        KVTC_W(24) KVTC_W(25) KVTC_W(26) KVTC_W(27) KVTC_W(28) KVTC_W(29) KVTC_W(30) KVTC_W(31)
+#define KVTC_W8(N) KVTC_W(N) KVTC_W(N + 1) KVTC_W(N + 2) KVTC_W(N + 3) KVTC_W(N + 4) KVTC_W(N + 5) KVTC_W(N + 6) KVTC_W(N + 7)
+    switch (n < 0 ? 0 : (n > 63 ? 63 : n)) {
+        KVTC_W8(0) KVTC_W8(8) KVTC_W8(16) KVTC_W8(24) KVTC_W8(32) KVTC_W8(40) KVTC_W8(48) KVTC_W8(56)
     }
+#undef KVTC_W8
 #undef KVTC_W
 }
 // Wait until at most k * N operations are in flight, k in 0..3 chosen at run time (wave-uniform).
