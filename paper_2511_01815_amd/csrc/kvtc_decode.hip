@@ -41,37 +41,74 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// Where the records of a tile sit in the LDS image.  Transfers move 16 bytes per lane (the
+// global->LDS path handles a lane at a time, so narrower pieces cost the same and carry less):
+//   * records of a whole number of 16-byte pieces, the tile starting on a 16-byte boundary of the
+//     stream (it does unless jobs with other record sizes precede it): each row gets an odd number of pieces (one or
+//     two of padding), which spreads the rows that 32 lanes unpack side by side over the banks
+//     (two lanes per bank at worst);
+//   * other record sizes: the tile's bytes are copied as they are, starting from the 16-byte
+//     boundary below the tile's first byte (`skew` dwords before it); the row stride is then rd
+//     dwords, which is not a multiple of four -- again two lanes per bank at worst.
+struct RecImage {
+    uint32_t stride_dw;     // LDS dwords from one row to the next
+    uint32_t skew_dw;       // LDS dwords before row 0
+    uint32_t pieces_row;    // padded scheme: pieces per row, padding included; 0 = verbatim copy
+};
+__device__ __forceinline__ RecImage rec_image(int rd, uint64_t tile_byte0) {
+    RecImage im;
+    if ((rd & 3) == 0 && (tile_byte0 & 15u) == 0u) {
+        const uint32_t m = (uint32_t)rd >> 2;
+        im.pieces_row = (m & 1u) ? m + 2u : m + 1u;
+        im.stride_dw = 4u * im.pieces_row;
+        im.skew_dw = 0u;
+    } else {
+        im.pieces_row = 0u;
+        im.stride_dw = (uint32_t)rd;
+        im.skew_dw = (uint32_t)(tile_byte0 & 15u) >> 2;
+    }
+    return im;
+}
+
 // Records of one workgroup tile (and the block table of its plan), global -> LDS, asynchronously
-// and without register staging: one dword per lane, 64 consecutive LDS dwords per instruction,
-// each fetched from wherever the padded row layout wants it (row stride rd + 1 dwords keeps the
-// unpacking loads of 32 lanes, one row each, on different banks).  Rows past the end of the tensor
-// replicate the last token's record, so every lane decodes something valid and the tail rows can
-// be stored unpredicated to the last token's place; the pad dword repeats the row's last dword
-// (never decoded).  Returns the number of transfers this wave issued; the caller owns the wait
-// (vmcnt) and the barrier that publishes the image.
+// and without register staging.  Only the tile's valid rows are fetched; rows past the end of the
+// tensor are never read (the unpacking redirects them to the last valid row).  Returns the number
+// of transfers this wave issued; the caller owns the wait (vmcnt) and the barrier that publishes
+// the image.
 __device__ __forceinline__ int issue_records(const KernelArgs& a, const TileRef& t, const PlanDec& P, uint32_t lds_work) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rd = P.rec_dwords, tok_wg = P.dec_tok_wg;
     const int tok0 = t.tile * tok_wg;
-    const uint32_t last_row = (uint32_t)(min(tok_wg, t.n_tokens - tok0) - 1);
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(a.stream_buf) + t.offset) + (size_t)tok0 * rd;
-    const uint32_t rstride = (uint32_t)rd + 1u;
-    const uint32_t total = (uint32_t)tok_wg * rstride;
-    const uint32_t magic = 0xffffffffu / rstride + 1u;
+    const uint32_t n_valid = (uint32_t)min(tok_wg, t.n_tokens - tok0);
+    const uint64_t byte0 = t.offset + (uint64_t)tok0 * (uint64_t)rd * 4ull;
+    const RecImage im = rec_image(rd, byte0);
+    const uint8_t* src = reinterpret_cast<const uint8_t*>(a.stream_buf) + (byte0 & ~15ull);
+    const uint32_t lds_rec = lds_work + kAuxBytes;
     int n = 0;
     if (wave == 0) {
         dma4_async(P.blk, (uint32_t)lane * 4u, lds_work);
         ++n;
     }
-    for (uint32_t l0 = (uint32_t)wave * 64u; l0 < total; l0 += kThreads) {
-        const uint32_t l = l0 + (uint32_t)lane;
-        if (l < total) {
-            const uint32_t row = __umulhi(l, magic);
-            const uint32_t w = l - row * rstride;
-            const uint32_t off = (min(row, last_row) * (uint32_t)rd + min(w, (uint32_t)rd - 1u)) * 4u;
-            dma4_async(src, off, lds_work + kAuxBytes + l0 * 4u);
+    if (im.pieces_row != 0u) {
+        const uint32_t m = (uint32_t)rd >> 2;
+        const uint32_t total = n_valid * im.pieces_row;          // LDS slots, padding included
+        const uint32_t magic = 0xffffffffu / im.pieces_row + 1u;
+        for (uint32_t l0 = (uint32_t)wave * 64u; l0 < total; l0 += kThreads) {
+            const uint32_t l = l0 + (uint32_t)lane;
+            if (l < total) {
+                const uint32_t row = __umulhi(l, magic);
+                const uint32_t col = l - row * im.pieces_row;
+                dma16_async(src, (row * m + min(col, m - 1u)) * 16u, lds_rec + l0 * 16u);    // padding repeats the last piece
+            }
+            ++n;
         }
-        ++n;
+    } else {
+        const uint32_t total = (im.skew_dw * 4u + n_valid * (uint32_t)rd * 4u + 15u) >> 4;   // pieces
+        for (uint32_t l0 = (uint32_t)wave * 64u; l0 < total; l0 += kThreads) {
+            const uint32_t l = l0 + (uint32_t)lane;
+            if (l < total) dma16_async(src, l * 16u, lds_rec + l0 * 16u);
+            ++n;
+        }
     }
     return n;
 }
@@ -97,7 +134,8 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
     const int T = tr.n_tokens;
     const int tok_tile0 = tr.tile * TOK_WG;
     const int rd = P.rec_dwords;
-    const int rstride = rd + 1;
+    const int n_valid = min(TOK_WG, T - tok_tile0);
+    const RecImage im = rec_image(rd, tr.offset + (uint64_t)tok_tile0 * (uint64_t)rd * 4ull);
     const int n_ft = p / 32;                                   // even: p is a multiple of 64
 
     // basis slab of feature tile ft -> ring stage; wave 0 also moves the tile's mu entries
@@ -116,7 +154,7 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
     // ---- each lane unpacks its blocks from the record image ------------------------------
     // A lane owns one token (l32) and, per 32-coordinate tile, the 16-coordinate block of its half h.
     const uint32_t* blk = reinterpret_cast<const uint32_t*>(work);
-    const uint32_t* rec = blk + kAuxBytes / 4;
+    const uint32_t* rec = blk + kAuxBytes / 4 + im.skew_dw;
     bf16x8 aop[TT][2 * NCT];
     // codes of up to 8 bits (all that calibration produces) come four to a 32-bit window, wider
     // ones two; the choice is made once per plan
@@ -131,7 +169,7 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
             const uint32_t pos0 = (info >> 16) * 16u;
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                const uint32_t* row = rec + (wave * TOK_W + tt * 32 + l32) * rstride;
+                const uint32_t* row = rec + (uint32_t)min(wave * TOK_W + tt * 32 + l32, n_valid - 1) * im.stride_dw;   // tail rows: the last token's record
                 const uint32_t hdr = bits != 0u ? row[g] : 0u;      // a block without bits decodes to zeros
                 const float shift = f16_bits_to_f32((uint16_t)(hdr & 0xffffu));
                 const float scale = f16_bits_to_f32((uint16_t)(hdr >> 16));
@@ -171,7 +209,6 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
     // so no store is ever predicated off and the number of memory operations per step is fixed.
     constexpr int NST = 16 * TT;                               // stores per pair of feature tiles
     const uint32_t ldb = (uint32_t)a.ld_x * (uint32_t)sizeof(OT);
-    const int n_valid = min(TOK_WG, T - tok_tile0);
     char* obase = reinterpret_cast<char*>(const_cast<void*>(a.x)) + (size_t)(tr.x_row0 + tok_tile0) * (size_t)a.ld_x * sizeof(OT);
     const uint32_t lane_row = (uint32_t)(wave * TOK_W + 4 * h);
     const uint32_t lane_col = (uint32_t)(2 * l32 * (int)sizeof(OT));
@@ -342,7 +379,7 @@ hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int gr
 // lays them out: side by side when both fit, else sharing the space).
 int decode_rec_bytes(int tt, int rec_dwords) {
     const int tok_wg = 4 * 32 * tt;
-    return kAuxBytes + (tok_wg * (rec_dwords + 1) * 4 + 255) / 256 * 256;      // whole 64-dword transfers
+    return kAuxBytes + (tok_wg * (rec_dwords + 8) * 4 + 16 + 1023) / 1024 * 1024;      // padded rows or skew + one piece; whole 64-piece transfers
 }
 int decode_ring_bytes(int nct) { return kDecStages * (2 * nct * 64 + kMuU4) * 16; }
 int decode_stage_u4(int nct) { return 2 * nct * 64 + kMuU4; }
