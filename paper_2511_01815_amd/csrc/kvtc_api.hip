@@ -220,7 +220,7 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     const size_t n_vdec = (size_t)(p / 32) * stage_u4 * 8;
     std::vector<uint16_t> venc, vdec;
     std::vector<float> negc, mu;
-    std::vector<uint32_t> blk(64, 0u), grp(n_groups, 0u);
+    std::vector<uint32_t> blk(64, 0u), grp(64, 0u);      // whole tables: the kernels fetch all 64 entries
     try {
         venc.assign(n_venc, 0);
         vdec.assign(n_vdec, 0);

@@ -172,6 +172,31 @@ __device__ __forceinline__ PlanDec load_plan_dec(const PlanDev* P) {
     return d;
 }
 
+// The fields of a plan descriptor the encode kernel uses, in scalar registers.
+struct PlanEnc {
+    int32_t p, n_groups, rec_dwords, enc_ntw, enc_wc;
+    const uint4* v_enc;
+    const float* negc;
+    const uint32_t* blk;
+    const uint32_t* grp;
+};
+__device__ __forceinline__ PlanEnc load_plan_enc(const PlanDev* P) {
+    static_assert(offsetof(PlanDev, n_groups) == 8 && offsetof(PlanDev, enc_ntw) == 20 && offsetof(PlanDev, enc_wc) == 24, "descriptor layout");
+    const char* b = reinterpret_cast<const char*>(P);
+    const u32x4 q0 = sload_x4(b), q1 = sload_x4(b + 16);
+    PlanEnc d;
+    d.p = (int32_t)q0[0];
+    d.n_groups = (int32_t)q0[2];
+    d.rec_dwords = (int32_t)q1[0];
+    d.enc_ntw = (int32_t)q1[1];
+    d.enc_wc = (int32_t)q1[2];
+    d.v_enc = sload_ptr<const uint4>(b + offsetof(PlanDev, v_enc));
+    d.negc = sload_ptr<const float>(b + offsetof(PlanDev, negc));
+    d.blk = sload_ptr<const uint32_t>(b + offsetof(PlanDev, blk));
+    d.grp = sload_ptr<const uint32_t>(b + offsetof(PlanDev, grp));
+    return d;
+}
+
 __device__ inline TileRef find_tile(const KernelArgs& a, const uint32_t* tile_start, uint32_t tile) {
     const int n_jobs = a.jobs ? a.n_jobs : 1;
     int lo = 0, hi = n_jobs;                 // invariant: tile_start[lo] <= tile < tile_start[hi]

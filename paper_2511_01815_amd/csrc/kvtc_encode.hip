@@ -72,9 +72,17 @@ __device__ __forceinline__ void put_bits(uint32_t* rec, uint32_t pos, uint32_t v
 __host__ __device__ constexpr int enc_ks(int ntp) { return ntp <= 8 || (ntp > 10 && ntp <= 16) ? 2 : 1; }
 __host__ __device__ constexpr int enc_stages(int ntp) { return enc_ks(ntp) == 2 ? 3 : 4; }
 
+// LDS work area (behind the job table): [tables of the tile's plan: block table 64 dwords, group
+// table 64 dwords, -(mu^T V_kept) of the padded coordinates][ring / epilogue images].  The tables
+// arrive by asynchronous transfers at the start of a tile, ahead of the first ring stage, so
+// no load of the tile loop is visible to the compiler (a visible vector load makes it wait for
+// everything in flight, and costs an L2 round trip where it stands).
+constexpr int kEncBlkOff = 0, kEncGrpOff = 256, kEncNegcOff = 512;
+__host__ __device__ constexpr int enc_aux_bytes(int ntp) { return 512 + ntp * 32 * 4; }
+
 template <int NTW, int WC, typename XT>
-__device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const TileRef& tr,
-                                            const KernelArgs& a, uint4* smem) {
+__device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
+                                            const KernelArgs& a, uint4* work) {
     constexpr int TT = 2;                    // token tiles (of 32) per wave
     constexpr int NTP = NTW * WC;            // coordinate tiles of the padded plan
     constexpr int WT = 4 / WC;               // waves across tokens
@@ -86,26 +94,22 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wc = wave % WC, wt = wave / WC;
     const int l32 = lane & 31, h = lane >> 5;
-    const int p = P->p;
+    const int p = P.p;
     const int T = tr.n_tokens;
     const int tok_tile0 = tr.tile * TOK_WG;
+    uint4* smem = work + enc_aux_bytes(NTP) / 16;
 
-    // ---- accumulators start at -(mu^T V_kept): centring folded into the product ------
-    f32x16 acc[TT][NTW];
+    // ---- the plan's tables -> LDS (first used in the epilogue) --------------------------
     {
-        const float* negc = P->negc + (wc * NTW) * 32 + 16 * h;
-#pragma unroll
-        for (int ct = 0; ct < NTW; ++ct) {
-            f32x16 c;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = *reinterpret_cast<const float4*>(negc + ct * 32 + 4 * q);
-                c[4 * q] = v.x; c[4 * q + 1] = v.y; c[4 * q + 2] = v.z; c[4 * q + 3] = v.w;
-            }
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) acc[tt][ct] = c;
-        }
+        const uint32_t aux = lds_offset(work);
+        if (wave == 0) dma4_async(P.blk, (uint32_t)lane * 4u, aux + kEncBlkOff);
+        if (wave == 1) dma4_async(P.grp, (uint32_t)lane * 4u, aux + kEncGrpOff);       // 64 entries allocated
+        static_assert(NTP * 8 <= kThreads, "one 16-byte piece per thread covers -(mu^T V_kept)");
+        if (wave * 64 < NTP * 8 && tid < NTP * 8)
+            dma16_async(P.negc, (uint32_t)tid * 16u, aux + kEncNegcOff + (uint32_t)wave * 1024u);
     }
+
+    f32x16 acc[TT][NTW];
 
     // ---- LDS: a ring of NSTAGE stages, each one basis slab and one X slab ----------
     using XS = XSlab<XT, KS>;
@@ -119,7 +123,7 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
     static_assert(TOK_WG % XS::ROWS_PER_DMA == 0, "whole transfers");
     static_assert(3 * (NV + NXD) < 64, "vmcnt range");
     char* ring = reinterpret_cast<char*>(smem);
-    const uint4* vg = P->v_enc;
+    const uint4* vg = P.v_enc;
     const int n_slabs = p / (16 * KS);
 
     // per-lane source of each X transfer: row (clamped at the tensor's end) and swizzled column
@@ -181,8 +185,24 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
 #pragma unroll
     for (int u = 0; u < D; ++u)
         if (u < n_slabs) issue(u, u);
-    wait_vmem_times<NDMA_MIN>(min(D - 1, n_slabs - 1));         // stage 0 has landed
+    wait_vmem_times<NDMA_MIN>(min(D - 1, n_slabs - 1));         // stage 0 has landed, and the tables before it
     __syncthreads();
+
+    // ---- accumulators start at -(mu^T V_kept): centring folded into the product ------
+    {
+        const float* negc = reinterpret_cast<const float*>(work) + kEncNegcOff / 4 + (wc * NTW) * 32 + 16 * h;
+#pragma unroll
+        for (int ct = 0; ct < NTW; ++ct) {
+            f32x16 c;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = *reinterpret_cast<const float4*>(negc + ct * 32 + 4 * q);
+                c[4 * q] = v.x; c[4 * q + 1] = v.y; c[4 * q + 2] = v.z; c[4 * q + 3] = v.w;
+            }
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) acc[tt][ct] = c;
+        }
+    }
     for (int s0 = 0; s0 < n_slabs; s0 += NSTAGE) {
 #pragma unroll
         for (int u = 0; u < NSTAGE; ++u) {
@@ -199,8 +219,10 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
 
     // ---- epilogue -----------------------------------------------------------------
     // LDS: mm[2*NTP][TOK_WG] float2 | gq[G][TOK_WG] float2 | rec[TOK_WG][rd + 1] dwords
-    const int G = P->n_groups;
-    const int rd = P->rec_dwords;
+    const int G = P.n_groups;
+    const int rd = P.rec_dwords;
+    const uint32_t* blk_t = reinterpret_cast<const uint32_t*>(work) + kEncBlkOff / 4;
+    const uint32_t* grp_t = reinterpret_cast<const uint32_t*>(work) + kEncGrpOff / 4;
     const int rstride = rd + 1;                 // odd-ish pitch keeps lanes on distinct banks
     float2* mm = reinterpret_cast<float2*>(smem);
     float2* gq = mm + 2 * NTP * TOK_WG;
@@ -226,7 +248,7 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
     // B: one header per (token, group)
     for (int item = tid; item < TOK_WG * G; item += kThreads) {
         const int tw = item % TOK_WG, g = item / TOK_WG;
-        const uint32_t gi = P->grp[g];
+        const uint32_t gi = grp_t[g];
         const int b0 = gi & 0xff, nb = (gi >> 8) & 0xff, bits = (gi >> 16) & 0xff;
         float lo = __builtin_inff(), hi = -__builtin_inff();
         for (int k = 0; k < nb; ++k) {
@@ -243,7 +265,7 @@ __device__ __forceinline__ void encode_tile(const PlanDev* __restrict__ P, const
     // C: codes of the lane's blocks, OR-ed into the record image
 #pragma unroll
     for (int ct = 0; ct < NTW; ++ct) {
-        const uint32_t info = P->blk[2 * (wc * NTW + ct) + h];
+        const uint32_t info = blk_t[2 * (wc * NTW + ct) + h];
         const uint32_t bits = info & 0xffu;
         if (bits != 0u) {
             const uint32_t g = (info >> 8) & 0xffu;
@@ -308,9 +330,8 @@ __global__ void __launch_bounds__(kThreads, 2) kvtc_encode_kernel(const KernelAr
     const uint32_t total = build_tile_table<true, 0>(a, tile_start, reinterpret_cast<uint32_t*>(work));
     for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
         const TileRef tr = find_tile(a, tile_start, tile);
-        const PlanDev* P = a.plans + tr.plan;
-        const int key = __builtin_amdgcn_readfirstlane(P->enc_wc * 100 + P->enc_ntw);
-        switch (key) {
+        const PlanEnc P = load_plan_enc(a.plans + tr.plan);
+        switch (P.enc_wc * 100 + P.enc_ntw) {
 #define KVTC_CASE(WC, NTW) case (WC) * 100 + (NTW): encode_tile<NTW, WC, XT>(P, tr, a, work); break;
             KVTC_CASE(1, 2) KVTC_CASE(1, 4) KVTC_CASE(2, 3) KVTC_CASE(2, 4) KVTC_CASE(2, 5)
 #undef KVTC_CASE
@@ -327,9 +348,8 @@ __global__ void __launch_bounds__(kThreads, 1) kvtc_encode_wide_kernel(const Ker
     const uint32_t total = build_tile_table<true, 1>(a, tile_start, reinterpret_cast<uint32_t*>(work));
     for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
         const TileRef tr = find_tile(a, tile_start, tile);
-        const PlanDev* P = a.plans + tr.plan;
-        const int key = __builtin_amdgcn_readfirstlane(P->enc_wc * 100 + P->enc_ntw);
-        switch (key) {
+        const PlanEnc P = load_plan_enc(a.plans + tr.plan);
+        switch (P.enc_wc * 100 + P.enc_ntw) {
 #define KVTC_CASE(WC, NTW) case (WC) * 100 + (NTW): encode_tile<NTW, WC, XT>(P, tr, a, work); break;
             KVTC_CASE(2, 6) KVTC_CASE(2, 8) KVTC_CASE(2, 10) KVTC_CASE(4, 6) KVTC_CASE(4, 8)
 #undef KVTC_CASE
@@ -375,7 +395,7 @@ int encode_lds_bytes(int ntw, int wc, int n_groups, int rec_dwords, kvtc_dtype d
     const int tok_wg = 64 * (4 / wc);
     const int main_b = enc_stages(ntp) * (ks * ntp * 1024 + tok_wg * ks * (dtype == KVTC_BF16 ? 32 : 64));
     const int epi_b = tok_wg * (2 * ntp * 8 + n_groups * 8 + (rec_dwords + 1) * 4);
-    return main_b > epi_b ? main_b : epi_b;
+    return enc_aux_bytes(ntp) + (main_b > epi_b ? main_b : epi_b);
 }
 
 }  // namespace kvtc
