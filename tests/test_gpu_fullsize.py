@@ -1,0 +1,167 @@
+"""GPU parity at the full sizes of the workload list, in the launch configuration bench.py times.
+
+The oracle cannot run a 4 GiB cache in seconds, so each case checks
+  * sampled tokens (tile boundaries, first and last rows of jobs, random rows): the GPU's records and
+    reconstructions of exactly those rows against the oracle, token by token, to the same bars as the
+    small-size tests (tokens are independent, so a subset is checked exactly like a whole tensor);
+  * properties that hold at any size, on the whole output, computed on the GPU with torch:
+    relative reconstruction error of every job, the stream length from the GPU prefix sum, guard bytes
+    behind the stream and padding columns untouched.
+"""
+import numpy as np
+import pytest
+import torch
+
+import kvtc_oracle as ko
+import kvtc_synth as ks
+import paper_2511_01815_amd as kv
+from test_gpu_parity import DEV, _gpu_plan, check_recon, check_stream
+
+pytestmark = pytest.mark.gpu
+
+
+def _calibrate(workload, layer, kvi, cr):
+    wl = ks.WORKLOADS[workload]
+    L = ks.make_layer(ks.layer_spec(workload, layer, kvi))
+    C_ = ks.bf16_bits_to_f32(ks.draw_bf16(L, wl.n_calib, ks.CALIB_DRAW))
+    mu, V, S = ko.pca(C_)
+    oplan = ko.calibrate_from_pca(C_, mu, V, S, cr, errors=ko.dp_errors(C_, mu, V))[0]
+    return L, oplan
+
+
+def _sample_rows(n, rng, k_random=160):
+    """Rows worth checking in a job of n tokens: both ends, both sides of workgroup-tile boundaries (128 and 256
+    tokens), random ones."""
+    rows = {0, n - 1, n // 2}
+    for b in (128, 256, 512, (n // 128) * 128, (n // 256) * 256):
+        for d in (-1, 0, 1):
+            if 0 <= b + d < n:
+                rows.add(b + d)
+    rows.update(int(r) for r in rng.integers(0, n, size=min(k_random, n)))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def _rows_to_host(t, rows):
+    idx = torch.from_numpy(rows).to(t.device)
+    sub = t.index_select(0, idx)
+    if sub.dtype == torch.bfloat16:
+        return ks.bf16_bits_to_f32(sub.view(torch.int16).cpu().numpy().view(np.uint16))
+    return sub.cpu().numpy()
+
+
+def _run_batch(oplans, layers, plan_of_job, lens, seeds, pad=0):
+    """Generate the jobs' tensors on the GPU, run offsets + encode + decode in one launch each, and
+    return what the checks need."""
+    p = oplans[0].p
+    gplans = [_gpu_plan(o) for o in oplans]
+    batch = kv.Batch(gplans)
+    n_jobs = len(lens)
+    row0 = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int64)
+    total = int(np.sum(lens))
+    ld = p + pad
+    x = torch.full((total, ld), 7.0, dtype=torch.bfloat16, device=DEV)
+    for j in range(n_jobs):
+        if lens[j]:
+            tmp = ks.draw_bf16_torch(layers[plan_of_job[j]], int(lens[j]), int(seeds[j]), DEV)
+            x[row0[j]:row0[j] + lens[j], :p] = tmp
+            del tmp
+    jobs = kv.make_jobs(list(plan_of_job), [int(n) for n in lens], [int(r) for r in row0])
+    jobs_dev = torch.from_numpy(jobs.view(np.uint8)).to(DEV)
+    offs = torch.zeros(n_jobs + 1, dtype=torch.int64, device=DEV)
+    kv.kvtc_offsets(batch.handle, jobs_dev, n_jobs, offs)
+    want = np.concatenate([[0], np.cumsum([int(n) * oplans[i].record_bytes for n, i in zip(lens, plan_of_job)])])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(offs.cpu().numpy(), want)
+    cap = int(want[-1])
+    guard = 256
+    stream = torch.full((cap + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    status = torch.zeros(2, dtype=torch.int32, device=DEV)
+    kv.kvtc_encode_batch(batch.handle, jobs_dev, n_jobs, x, kv.KVTC_BF16, ld, offs, stream, cap, status[0:1])
+    x_hat = torch.full_like(x, 7.0)
+    kv.kvtc_decode_batch(batch.handle, jobs_dev, n_jobs, stream, cap, offs, x_hat, kv.KVTC_BF16, ld, status[1:2])
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    assert torch.all(stream[cap:] == 0xA5), "wrote past the stream"
+    if pad:
+        assert torch.all(x_hat[:, p:] == 7.0), "wrote into the row padding"
+    return dict(x=x, x_hat=x_hat, stream=stream, want=want, row0=row0, p=p)
+
+
+def _check_jobs(res, oplans, plan_of_job, lens, jobs_to_sample, rng, label, max_rel=0.3):
+    x, x_hat, stream, want, row0, p = (res[k] for k in ("x", "x_hat", "stream", "want", "row0", "p"))
+    # any-size property: relative reconstruction error of every job (what the compression ratio should give)
+    for j, n in enumerate(lens):
+        if n == 0:
+            continue
+        a = x[row0[j]:row0[j] + n, :p].float()
+        b = x_hat[row0[j]:row0[j] + n, :p].float()
+        rel = float((b - a).norm() / (a - a.mean(0)).norm())
+        assert rel < max_rel, (label, j, rel)
+    # sampled rows, token by token against the oracle
+    for j in jobs_to_sample:
+        n, o = int(lens[j]), oplans[plan_of_job[j]]
+        rows = _sample_rows(n, rng)
+        R = o.record_bytes
+        xv = _rows_to_host(x[row0[j]:row0[j] + n, :p], rows)
+        rec = stream[int(want[j]):int(want[j + 1])].view(n, R).index_select(0, torch.from_numpy(rows).to(DEV)).cpu().numpy()
+        xh = _rows_to_host(x_hat[row0[j]:row0[j] + n, :p], rows)
+        st = check_stream(o, xv, rec, f"{label}-job{j}")
+        st["recon"] = check_recon(o, rec, xh, xv, True, f"{label}-job{j}")
+    return st
+
+
+def test_bench_configuration_sampled():
+    """The batch bench.py times: K and V of the config-2 layer, 32768 tokens each, 32 seeded draws, 16x plans
+    from the committed calibration bundles, one launch per direction (4 GiB of raw KV)."""
+    import os
+    plans_dir = os.path.join(os.path.dirname(kv.__file__), "plans")
+    oplans = []
+    for name in ("c2_K_cr16", "c2_V_cr16"):
+        z = np.load(os.path.join(plans_dir, name + ".npz"))
+        oplans.append(ko.plan_from_arrays(z["mu32"], z["v_bits"], z["group_n"], z["group_bits"]))
+    layers = [ks.make_layer(ks.layer_spec("c2", 0, kvi)) for kvi in (0, 1)]
+    n_jobs, T = 64, 32768
+    res = _run_batch(oplans, layers, [j % 2 for j in range(n_jobs)], [T] * n_jobs, [10 + j // 2 for j in range(n_jobs)])
+    rng = np.random.default_rng(31)
+    st = _check_jobs(res, oplans, [j % 2 for j in range(n_jobs)], [T] * n_jobs, list(range(0, n_jobs, 3)) + [n_jobs - 1], rng, "bench")
+    print("bench configuration", st)
+
+
+@pytest.mark.parametrize("cr", [8.0, 20.0])
+def test_config3_per_layer_plans(cr):
+    """Full-cache shape: a separate plan per layer and per K/V (two of the 32 layers here, all four tensors at
+    the full 32768 tokens, in one batch), per-layer spectrum exponent; 8x uses the wide kernels, 20x records of
+    100 bytes (not a multiple of 16)."""
+    specs = [(3, 0), (3, 1), (17, 0), (17, 1)]
+    cal = [_calibrate("c3", l, kvi, cr) for l, kvi in specs]
+    layers, oplans = [c[0] for c in cal], [c[1] for c in cal]
+    T = ks.WORKLOADS["c3"].n_tokens
+    res = _run_batch(oplans, layers, [0, 1, 2, 3], [T] * 4, [ks.TEST_DRAW] * 4)
+    st = _check_jobs(res, oplans, [0, 1, 2, 3], [T] * 4, [0, 1, 2, 3], np.random.default_rng(33), f"c3@{cr}",
+                     max_rel=0.45)
+    print("config 3", cr, [o.r for o in oplans], [o.record_bytes for o in oplans], st)
+
+
+def test_config4_long_context_slice():
+    """Long-context shape: one layer's K and V at the full 131072 tokens, 20x."""
+    cal = [_calibrate("c4", 5, kvi, 20.0) for kvi in (0, 1)]
+    layers, oplans = [c[0] for c in cal], [c[1] for c in cal]
+    T = ks.WORKLOADS["c4"].n_tokens
+    res = _run_batch(oplans, layers, [0, 1], [T, T], [ks.TEST_DRAW, ks.TEST_DRAW], pad=8)
+    st = _check_jobs(res, oplans, [0, 1], [T, T], [0, 1], np.random.default_rng(34), "c4", max_rel=0.45)
+    print("config 4", [o.r for o in oplans], [o.record_bytes for o in oplans], st)
+
+
+def test_config5_ragged_batch():
+    """Ragged batch: 256 independent caches (log-uniform lengths), K and V of one layer = 512 jobs in one
+    launch per direction at 40x; stream offsets from the GPU prefix sum."""
+    cal = [_calibrate("c5", 9, kvi, 40.0) for kvi in (0, 1)]
+    layers, oplans = [c[0] for c in cal], [c[1] for c in cal]
+    lens_c = ks.ragged_lengths("c5")
+    lens = np.repeat(lens_c, 2)
+    plan_of_job = [j % 2 for j in range(len(lens))]
+    res = _run_batch(oplans, layers, plan_of_job, lens, [500 + j for j in range(len(lens))])
+    shortest, longest = int(np.argmin(lens)), int(np.argmax(lens))
+    st = _check_jobs(res, oplans, plan_of_job, lens, sorted({0, 1, shortest, longest, len(lens) - 1, 100, 301}),
+                     np.random.default_rng(35), "c5", max_rel=0.6)
+    print("config 5", len(lens), int(lens.sum()), [o.r for o in oplans], [o.record_bytes for o in oplans], st)

