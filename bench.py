@@ -70,7 +70,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--cr", type=int, default=16, choices=[8, 16, 20, 40])
+    ap.add_argument("--cr", default="16", choices=["8", "16", "20", "40", "full"],
+                    help="compression target of the calibrated plans; 'full' = hand-set full-rank plan (compute-bound)")
     ap.add_argument("--layers", type=int, default=32, help="independent draws of the layer per batch")
     ap.add_argument("--tokens", type=int, default=32768)
     ap.add_argument("--cpu-tokens", type=int, default=32768, help="tokens per tensor in the CPU-baseline sample")
@@ -96,7 +97,8 @@ def main() -> int:
     torch.cuda.set_device(dev)
     p, T, NL = 1024, args.tokens, args.layers
 
-    bundles = [load_bundle(f"c2_K_cr{args.cr}"), load_bundle(f"c2_V_cr{args.cr}")]
+    tag = "full" if args.cr == "full" else f"cr{args.cr}"
+    bundles = [load_bundle(f"c2_K_{tag}"), load_bundle(f"c2_V_{tag}")]
     plans = [kv.Plan(p, b["v_bits"].shape[1], b["mu32"], b["v_bits"],
                      list(zip(b["group_n"].tolist(), b["group_bits"].tolist()))) for b in bundles]
     batch = kv.Batch(plans)
@@ -157,7 +159,7 @@ def main() -> int:
         a = x[:T].float()
         b = x_hat[:T].float()
         rel = float((b - a).norm() / (a - a.mean(0)).norm())
-    assert rel < 0.25, rel
+    assert rel < (0.25 if args.cr in ("8", "16", "full") else 0.5), rel
 
     # ---- roofline of the dominant kernel (per launch) ----
     alg_bytes = sum(T * (2 * p + R[j % 2]) for j in range(n_jobs))
@@ -174,7 +176,7 @@ def main() -> int:
     # what the same counter reads for a 4 GiB copy): measured offline on the default workload only,
     # see profiles/kvtc_kernels_c2x32_cr16.md
     measured = {"kvtc_encode_kernel": 4.55 * 2**30, "kvtc_decode_kernel": 4.49 * 2**30}
-    default_workload = args.cr == 16 and NL == 32 and T == 32768
+    default_workload = args.cr == "16" and NL == 32 and T == 32768
     roof["traffic"] = measured[dom] if default_workload else None
     roof["kernel"] = dom
     roof["encode"] = dict(ms=enc_avg, raw_GBps=raw_bytes / enc_avg / 1e6,
@@ -191,10 +193,10 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"c2 layer (K+V, {T} tok x 1024 bf16, {args.cr}x, r={r[0]}/{r[1]}, R={R[0]}/{R[1]} B) "
+        "config": {"workload": f"c2 layer (K+V, {T} tok x 1024 bf16, {args.cr if args.cr == 'full' else args.cr + 'x'}, r={r[0]}/{r[1]}, R={R[0]}/{R[1]} B) "
                                f"x {NL} seeded draws in one batch = {raw_bytes / 2**30:.2f} GiB raw KV; "
                                "step = offsets + encode + decode",
-                   "compression": args.cr, "n_jobs": n_jobs},
+                   "compression": 2.0 * p / R[0], "n_jobs": n_jobs},
         "roofline": roof,
     }
     if not args.no_cpu:

@@ -35,6 +35,16 @@ def main() -> None:
             ko.save_plan(path, plan, cr=cr, budget_bits=info["budget_bits"], seed=spec.seed, alpha=spec.alpha)
             print(path, "r", plan.r, "R", plan.record_bytes,
                   list(zip(plan.group_n.tolist(), plan.group_bits.tolist())))
+        # a full-rank plan (every PCA coordinate kept, hand-set widths, about 3.8x) for the compute-bound
+        # end of the roofline: the projection is then the whole p x p product
+        blocks, start = [], 0
+        for n, b in ((64, 8), (192, 6), (256, 4), (512, 3)):
+            blocks.append(ko.Block(start, n, b))
+            start += n
+        plan = ko.compile_plan(mu, V, blocks)
+        path = os.path.join(out_dir, f"c2_{name}_full.npz")
+        ko.save_plan(path, plan, cr=2.0 * wl.p / plan.record_bytes, budget_bits=8 * plan.record_bytes, seed=spec.seed, alpha=spec.alpha)
+        print(path, "r", plan.r, "R", plan.record_bytes)
 
 
 if __name__ == "__main__":

@@ -14,8 +14,8 @@
 #include "kvtc_numeric.h"
 
 namespace kvtc {
-hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream);
-hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream);
+hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream);
+hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream);
 int encode_lds_bytes(int ntw, int wc, int n_groups, int rec_dwords, kvtc_dtype dtype);
 int decode_rec_bytes(int tt, int rec_dwords);
 int decode_ring_bytes(int nct);
@@ -34,8 +34,11 @@ struct kvtc_plan {
 struct kvtc_batch {
     PlanDev* plans_dev;
     int n_plans;
-    int enc_lds[2][2];                  // max over the plans of each kernel flavour (narrow, wide) and element dtype; -1: none
-    int dec_rec[2], dec_ring[2];        // decode, per kernel flavour: max record image, max basis ring + mu; -1: none
+    // the kernel variants the plans use (a launch per variant), with the LDS maxima over each one's plans
+    struct EncVariant { int key, wide, lds[2]; };       // lds per element dtype
+    struct DecVariant { int key, wide, rec, ring; };    // record image, basis ring
+    std::vector<EncVariant> enc;
+    std::vector<DecVariant> dec;
     int max_p;
     std::vector<int32_t> rec_dwords;
     uint32_t* rec_dwords_dev;
@@ -193,7 +196,7 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
         if (e[0] * e[1] >= nt) { d.enc_wc = e[0]; d.enc_ntw = e[1]; d.enc_wide = e[2]; break; }
     // {token tiles per wave, coordinate tiles, wide kernel?}
     static const int dec_tab[][3] = {{2, 2, 0}, {2, 4, 0}, {2, 6, 0}, {2, 8, 0}, {2, 10, 0},
-                                     {1, 12, 1}, {1, 16, 1}, {1, 20, 1}, {1, 24, 1}, {1, 32, 1}};
+                                     {2, 12, 1}, {2, 16, 1}, {2, 20, 1}, {2, 24, 1}, {1, 32, 1}};
     d.dec_tt = 0;
     for (auto& e : dec_tab)
         if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; d.dec_wide = e[2]; break; }
@@ -370,7 +373,7 @@ kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dty
     const int64_t tiles = (n_tokens + plan->h.enc_tok_wg - 1) / plan->h.enc_tok_wg;
     const int slots = cu_count() * (plan->h.enc_wide ? 1 : 2);
     const int grid = (int)(tiles < slots ? tiles : slots);
-    hipError_t e = launch_encode(a, dtype, plan->h.enc_wide, grid, (size_t)kJobTableBytes + 64 + plan->h.enc_lds[dtype], static_cast<hipStream_t>(stream));
+    hipError_t e = launch_encode(a, dtype, plan->h.enc_wc * 100 + plan->h.enc_ntw, grid, (size_t)kJobTableBytes + 64 + plan->h.enc_lds[dtype], static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }
@@ -401,7 +404,7 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
     const int grid = (int)(tiles < slots ? tiles : slots);
     const DecLayout lay = decode_layout(plan->h.dec_rec_lds, plan->h.dec_ring_lds, plan->h.dec_wide);
     a.dec_ring_off = lay.ring_off;
-    hipError_t e = launch_decode(a, dtype, plan->h.dec_wide, grid, lay.lds_bytes, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_decode(a, dtype, plan->h.dec_tt * 100 + plan->h.dec_nct, grid, lay.lds_bytes, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }
@@ -415,10 +418,8 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
     b->plans_dev = nullptr;
     b->rec_dwords_dev = nullptr;
     b->n_plans = n_plans;
-    for (int f = 0; f < 2; ++f)
-        for (int dt = 0; dt < 2; ++dt) b->enc_lds[f][dt] = -1;
-    b->dec_rec[0] = b->dec_rec[1] = b->dec_ring[0] = b->dec_ring[1] = -1;
     b->max_p = 0;
+    try {
     for (int i = 0; i < n_plans; ++i) {
         if (!plans[i]) {
             delete b;
@@ -427,11 +428,35 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
         h.push_back(plans[i]->h);
         b->rec_dwords.push_back(plans[i]->h.rec_dwords);
         const PlanDev& ph = plans[i]->h;
-        for (int dt = 0; dt < 2; ++dt)
-            if (ph.enc_lds[dt] > b->enc_lds[ph.enc_wide][dt]) b->enc_lds[ph.enc_wide][dt] = ph.enc_lds[dt];
-        if (ph.dec_rec_lds > b->dec_rec[ph.dec_wide]) b->dec_rec[ph.dec_wide] = ph.dec_rec_lds;
-        if (ph.dec_ring_lds > b->dec_ring[ph.dec_wide]) b->dec_ring[ph.dec_wide] = ph.dec_ring_lds;
+        {
+            const int key = ph.enc_wc * 100 + ph.enc_ntw;
+            kvtc_batch::EncVariant* v = nullptr;
+            for (auto& e : b->enc)
+                if (e.key == key) v = &e;
+            if (!v) {
+                b->enc.push_back({key, ph.enc_wide, {0, 0}});
+                v = &b->enc.back();
+            }
+            for (int dt = 0; dt < 2; ++dt)
+                if (ph.enc_lds[dt] > v->lds[dt]) v->lds[dt] = ph.enc_lds[dt];
+        }
+        {
+            const int key = ph.dec_tt * 100 + ph.dec_nct;
+            kvtc_batch::DecVariant* v = nullptr;
+            for (auto& e : b->dec)
+                if (e.key == key) v = &e;
+            if (!v) {
+                b->dec.push_back({key, ph.dec_wide, 0, 0});
+                v = &b->dec.back();
+            }
+            if (ph.dec_rec_lds > v->rec) v->rec = ph.dec_rec_lds;
+            if (ph.dec_ring_lds > v->ring) v->ring = ph.dec_ring_lds;
+        }
         if (ph.p > b->max_p) b->max_p = ph.p;
+    }
+    } catch (const std::bad_alloc&) {
+        delete b;
+        return fail(KVTC_E_NOMEM, "kvtc_batch_create: host allocation failed");
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&b->plans_dev), sizeof(PlanDev) * n_plans);
@@ -508,10 +533,9 @@ kvtc_status kvtc_encode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.cap = out_cap;
     a.status = status_dev;
     if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_encode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
-    for (int wide = 0; wide < 2; ++wide) {
-        if (batch->enc_lds[wide][dtype] < 0) continue;      // no plan of this flavour
-        hipError_t e = launch_encode(a, dtype, wide, cu_count() * (wide ? 1 : 2),
-                                     (size_t)kJobTableBytes + 64 + batch->enc_lds[wide][dtype], static_cast<hipStream_t>(stream));
+    for (const auto& v : batch->enc) {
+        hipError_t e = launch_encode(a, dtype, v.key, cu_count() * (v.wide ? 1 : 2),
+                                     (size_t)kJobTableBytes + 64 + v.lds[dtype], static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode_batch: launch failed: %s", hipGetErrorString(e));
     }
     return KVTC_OK;
@@ -537,11 +561,10 @@ kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.cap = in_bytes;
     a.status = status_dev;
     if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_decode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
-    for (int wide = 0; wide < 2; ++wide) {
-        if (batch->dec_rec[wide] < 0) continue;
-        const DecLayout lay = decode_layout(batch->dec_rec[wide], batch->dec_ring[wide], wide);
+    for (const auto& v : batch->dec) {
+        const DecLayout lay = decode_layout(v.rec, v.ring, v.wide);
         a.dec_ring_off = lay.ring_off;
-        hipError_t e = launch_decode(a, dtype, wide, cu_count() * (wide ? 1 : 2), lay.lds_bytes, static_cast<hipStream_t>(stream));
+        hipError_t e = launch_decode(a, dtype, v.key, cu_count() * (v.wide ? 1 : 2), lay.lds_bytes, static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode_batch: launch failed: %s", hipGetErrorString(e));
     }
     return KVTC_OK;

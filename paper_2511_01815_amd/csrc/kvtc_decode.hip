@@ -277,14 +277,21 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
     }
 }
 
-// The persistent tile loop shared by both kernels.  With a non-zero a.dec_ring_off the ring sits
-// behind the record image and each tile's records are fetched during the previous tile's sweep;
-// with offset 0 they share the space and the records are fetched at the tile's start.
-template <typename OT, int kWide, typename Dispatch>
-__device__ __forceinline__ void decode_loop(const KernelArgs& a, uint4* smem, Dispatch dispatch) {
+// One kernel per variant (TT token tiles per wave, NCT coordinate tiles): narrow plans (up to 320
+// padded coordinates) run two workgroups per compute unit, wide ones get the whole register file
+// (two token tiles per wave up to 768 padded coordinates, one beyond).  A batched launch serves only
+// the jobs whose plan uses its variant.  The tile loop is persistent.  With a non-zero
+// a.dec_ring_off the ring sits behind the record image and each tile's records are fetched during
+// the previous tile's sweep; with offset 0 they share the space and the records are fetched at the
+// tile's start.
+template <int TT, int NCT> constexpr int dec_wgs_per_cu() { return NCT <= 10 ? 2 : 1; }
+
+template <typename OT, int TT, int NCT>
+__global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, NCT>())) kvtc_decode_kernel(const KernelArgs a) {
+    extern __shared__ uint4 smem[];
     uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
     uint4* work = smem + kJobTableBytes / 16 + 1;
-    const uint32_t total = build_tile_table<false, kWide>(a, tile_start, reinterpret_cast<uint32_t*>(work));
+    const uint32_t total = build_tile_table<false>(a, TT * 100 + NCT, tile_start, reinterpret_cast<uint32_t*>(work));
     uint32_t tile = blockIdx.x;
     if (tile >= total) return;
     const bool prefetch = a.dec_ring_off != 0u;
@@ -303,7 +310,7 @@ __device__ __forceinline__ void decode_loop(const KernelArgs& a, uint4* smem, Di
             trn = find_tile(a, tile_start, next);
             Pn = load_plan_dec(a.plans + trn.plan);
         }
-        dispatch(P.dec_tt * 100 + P.dec_nct, P, tr, work, ring, prefetch, has_next && prefetch, trn, Pn);
+        decode_tile<NCT, TT, OT>(P, tr, a, work, ring, prefetch, has_next && prefetch, trn, Pn);
         if (!has_next) break;
         tile = next;
         tr = trn;
@@ -316,63 +323,26 @@ __device__ __forceinline__ void decode_loop(const KernelArgs& a, uint4* smem, Di
     }
 }
 
-// Two kernels, as for encode: narrow plans (two token tiles per wave, up to 320 padded
-// coordinates) run two workgroups per compute unit, wide ones get the whole register file.
-#define KVTC_DISPATCH_ARGS int key, const PlanDec& P, const TileRef& tr, uint4* work, uint4* ring, bool prefetch, bool has_next, \
-                           const TileRef& next, const PlanDec& Pn
-#define KVTC_CASE(TT, NCT) \
-    case (TT) * 100 + (NCT): decode_tile<NCT, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break;
-template <typename OT>
-__global__ void __launch_bounds__(kThreads, 2) kvtc_decode_kernel(const KernelArgs a) {
-    extern __shared__ uint4 smem[];
-    decode_loop<OT, 0>(a, smem, [&](KVTC_DISPATCH_ARGS) {
-        switch (key) {
-            KVTC_CASE(2, 2) KVTC_CASE(2, 4) KVTC_CASE(2, 6) KVTC_CASE(2, 8) KVTC_CASE(2, 10)
-            default: break;
-        }
-    });
-}
+#define KVTC_DEC_VARIANTS(X) X(2, 2) X(2, 4) X(2, 6) X(2, 8) X(2, 10) X(2, 12) X(2, 16) X(2, 20) X(2, 24) X(1, 32)
 
-template <typename OT>
-__global__ void __launch_bounds__(kThreads, 1) kvtc_decode_wide_kernel(const KernelArgs a) {
-    extern __shared__ uint4 smem[];
-    decode_loop<OT, 1>(a, smem, [&](KVTC_DISPATCH_ARGS) {
-        switch (key) {
-            KVTC_CASE(1, 12) KVTC_CASE(1, 16) KVTC_CASE(1, 20) KVTC_CASE(1, 24) KVTC_CASE(1, 32)
-            default: break;
-        }
-    });
-}
-#undef KVTC_CASE
-#undef KVTC_DISPATCH_ARGS
-
-template <typename K>
-static hipError_t set_lds_attr_d(K kernel) {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
-}
-
-hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = set_lds_attr_d(&kvtc_decode_kernel<uint16_t>);
-        if (e == hipSuccess) e = set_lds_attr_d(&kvtc_decode_kernel<float>);
-        if (e == hipSuccess) e = set_lds_attr_d(&kvtc_decode_wide_kernel<uint16_t>);
-        if (e == hipSuccess) e = set_lds_attr_d(&kvtc_decode_wide_kernel<float>);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+// key = 100 * TT + NCT
+hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream) {
+    const void* fn = nullptr;
+    switch (key) {
+#define KVTC_X(TT, NCT)                                                                                        \
+    case (TT) * 100 + (NCT):                                                                                   \
+        fn = dtype == KVTC_BF16 ? reinterpret_cast<const void*>(&kvtc_decode_kernel<uint16_t, TT, NCT>)        \
+                                : reinterpret_cast<const void*>(&kvtc_decode_kernel<float, TT, NCT>);          \
+        break;
+        KVTC_DEC_VARIANTS(KVTC_X)
+#undef KVTC_X
+        default: return hipErrorInvalidValue;
     }
-    if (!wide) {
-        if (dtype == KVTC_BF16)
-            hipLaunchKernelGGL(kvtc_decode_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
-        else
-            hipLaunchKernelGGL(kvtc_decode_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
-    } else {
-        if (dtype == KVTC_BF16)
-            hipLaunchKernelGGL(kvtc_decode_wide_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
-        else
-            hipLaunchKernelGGL(kvtc_decode_wide_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
-    }
-    return hipGetLastError();
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+    if (e != hipSuccess) return e;
+    KernelArgs args = a;
+    void* params[] = {&args};
+    return hipLaunchKernel(fn, dim3(grid), dim3(kThreads), params, lds_bytes, stream);
 }
 
 // Bytes of the block table + record image and of the basis ring of a decode variant (the host

@@ -24,7 +24,7 @@ struct PlanDev {
     int32_t enc_lds[2];                     // encode: dynamic LDS bytes needed (without the job table), per element dtype
     int32_t dec_rec_lds, dec_ring_lds;      // decode: bytes of the record image, of the basis ring + mu
     int32_t code_bits_max;                  // widest code of the plan
-    int32_t enc_wide, dec_wide;             // 0: served by the two-waves-per-SIMD kernel, 1: by the 512-register one
+    int32_t enc_wide, dec_wide;             // 0: the variant runs two waves per SIMD (256 registers), 1: one (512)
     const uint4* v_enc;    // [p/16][32*ntp/32][64] MFMA A fragments of V_kept^T (encode)
     const uint4* v_dec;    // [p/32][2*nct*64 + 16] MFMA B fragments of V_kept^T (decode), then the tile's 32 mu entries; tiles 2k, 2k+1 = even, odd features of span k
     const float* negc;     // [32*ntp]  -(mu^T V_kept), zero in the padding
@@ -57,9 +57,10 @@ struct TileRef {
 
 // Builds the exclusive prefix of tiles per job in LDS (tile_start[0..n_jobs]) and returns
 // the total.  A job with a bad plan index, a negative token count or a stream that would end
-// beyond `cap` gets zero tiles; workgroup 0 reports the lowest such job in *status.
-template <bool kEncode, int kWide>
-__device__ inline uint32_t build_tile_table(const KernelArgs& a, uint32_t* tile_start, uint32_t* scratch /*[kThreads + 1]*/) {
+// beyond `cap` gets zero tiles, and so does a job whose plan belongs to another kernel variant
+// (variant_key: 100 * first + second variant parameter); workgroup 0 reports the lowest bad job in *status.
+template <bool kEncode>
+__device__ inline uint32_t build_tile_table(const KernelArgs& a, int variant_key, uint32_t* tile_start, uint32_t* scratch /*[kThreads + 1]*/) {
     const int tid = threadIdx.x;
     const int n_jobs = a.jobs ? a.n_jobs : 1;
     const int per = (n_jobs + kThreads - 1) / kThreads;
@@ -78,8 +79,9 @@ __device__ inline uint32_t build_tile_table(const KernelArgs& a, uint32_t* tile_
             if (ok) {
                 const PlanDev& pl = a.plans[jb.plan];
                 const int tw = kEncode ? pl.enc_tok_wg : pl.dec_tok_wg;
-                // each launch serves the plans of its own kernel flavour; the other launch takes the rest
-                if ((kEncode ? pl.enc_wide : pl.dec_wide) == kWide) tiles = (uint32_t)((jb.n_tokens + tw - 1) / tw);
+                // each launch serves the plans of its own kernel variant; other launches take the rest
+                if ((kEncode ? pl.enc_wc * 100 + pl.enc_ntw : pl.dec_tt * 100 + pl.dec_nct) == variant_key)
+                    tiles = (uint32_t)((jb.n_tokens + tw - 1) / tw);
             } else if (first_bad == 0xffffffffu) {
                 first_bad = (uint32_t)j;
             }

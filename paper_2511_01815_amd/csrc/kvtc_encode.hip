@@ -319,73 +319,45 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
     __syncthreads();
 }
 
-// Two kernels: plans of up to 320 padded coordinates fit in 256 registers per lane and run two
-// workgroups per compute unit (one hides the other's memory waits and epilogue); wider plans
-// get the whole register file.  A batched launch serves only the plans of its own flavour.
-template <typename XT>
-__global__ void __launch_bounds__(kThreads, 2) kvtc_encode_kernel(const KernelArgs a) {
+// One kernel per variant (WC waves across coordinates, NTW coordinate tiles per wave): plans of up
+// to 320 padded coordinates fit in 256 registers per lane and run two workgroups per compute unit
+// (one hides the other's memory waits and epilogue); wider plans get the whole register file.  A
+// batched launch serves only the jobs whose plan uses its variant.
+template <int WC, int NTW> constexpr int enc_wgs_per_cu() { return WC * NTW <= 10 ? 2 : 1; }
+
+template <typename XT, int WC, int NTW>
+__global__ void __launch_bounds__(kThreads, (enc_wgs_per_cu<WC, NTW>())) kvtc_encode_kernel(const KernelArgs a) {
     extern __shared__ uint4 smem[];
     uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
     uint4* work = smem + kJobTableBytes / 16 + 1;
-    const uint32_t total = build_tile_table<true, 0>(a, tile_start, reinterpret_cast<uint32_t*>(work));
+    const uint32_t total = build_tile_table<true>(a, WC * 100 + NTW, tile_start, reinterpret_cast<uint32_t*>(work));
     for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
         const TileRef tr = find_tile(a, tile_start, tile);
         const PlanEnc P = load_plan_enc(a.plans + tr.plan);
-        switch (P.enc_wc * 100 + P.enc_ntw) {
-#define KVTC_CASE(WC, NTW) case (WC) * 100 + (NTW): encode_tile<NTW, WC, XT>(P, tr, a, work); break;
-            KVTC_CASE(1, 2) KVTC_CASE(1, 4) KVTC_CASE(2, 3) KVTC_CASE(2, 4) KVTC_CASE(2, 5)
-#undef KVTC_CASE
-            default: break;
-        }
+        encode_tile<NTW, WC, XT>(P, tr, a, work);
     }
 }
 
-template <typename XT>
-__global__ void __launch_bounds__(kThreads, 1) kvtc_encode_wide_kernel(const KernelArgs a) {
-    extern __shared__ uint4 smem[];
-    uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
-    uint4* work = smem + kJobTableBytes / 16 + 1;
-    const uint32_t total = build_tile_table<true, 1>(a, tile_start, reinterpret_cast<uint32_t*>(work));
-    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
-        const TileRef tr = find_tile(a, tile_start, tile);
-        const PlanEnc P = load_plan_enc(a.plans + tr.plan);
-        switch (P.enc_wc * 100 + P.enc_ntw) {
-#define KVTC_CASE(WC, NTW) case (WC) * 100 + (NTW): encode_tile<NTW, WC, XT>(P, tr, a, work); break;
-            KVTC_CASE(2, 6) KVTC_CASE(2, 8) KVTC_CASE(2, 10) KVTC_CASE(4, 6) KVTC_CASE(4, 8)
-#undef KVTC_CASE
-            default: break;
-        }
-    }
-}
+#define KVTC_ENC_VARIANTS(X) X(1, 2) X(1, 4) X(2, 3) X(2, 4) X(2, 5) X(2, 6) X(2, 8) X(2, 10) X(4, 6) X(4, 8)
 
-template <typename K>
-static hipError_t set_lds_attr(K kernel) {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
-}
-
-// wide = 0: the two-waves-per-SIMD kernel, 1: the 512-register kernel.
-hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int wide, int grid, size_t lds_bytes, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = set_lds_attr(&kvtc_encode_kernel<uint16_t>);
-        if (e == hipSuccess) e = set_lds_attr(&kvtc_encode_kernel<float>);
-        if (e == hipSuccess) e = set_lds_attr(&kvtc_encode_wide_kernel<uint16_t>);
-        if (e == hipSuccess) e = set_lds_attr(&kvtc_encode_wide_kernel<float>);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+// key = 100 * WC + NTW
+hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream) {
+    const void* fn = nullptr;
+    switch (key) {
+#define KVTC_X(WC, NTW)                                                                                        \
+    case (WC) * 100 + (NTW):                                                                                   \
+        fn = dtype == KVTC_BF16 ? reinterpret_cast<const void*>(&kvtc_encode_kernel<uint16_t, WC, NTW>)        \
+                                : reinterpret_cast<const void*>(&kvtc_encode_kernel<float, WC, NTW>);          \
+        break;
+        KVTC_ENC_VARIANTS(KVTC_X)
+#undef KVTC_X
+        default: return hipErrorInvalidValue;
     }
-    if (!wide) {
-        if (dtype == KVTC_BF16)
-            hipLaunchKernelGGL(kvtc_encode_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
-        else
-            hipLaunchKernelGGL(kvtc_encode_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
-    } else {
-        if (dtype == KVTC_BF16)
-            hipLaunchKernelGGL(kvtc_encode_wide_kernel<uint16_t>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
-        else
-            hipLaunchKernelGGL(kvtc_encode_wide_kernel<float>, dim3(grid), dim3(kThreads), lds_bytes, stream, a);
-    }
-    return hipGetLastError();
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+    if (e != hipSuccess) return e;
+    KernelArgs args = a;
+    void* params[] = {&args};
+    return hipLaunchKernel(fn, dim3(grid), dim3(kThreads), params, lds_bytes, stream);
 }
 
 // LDS bytes encode_tile needs for a variant (main loop slabs vs epilogue images).
