@@ -16,7 +16,7 @@
 namespace kvtc {
 hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream);
 hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream);
-int encode_lds_bytes(int ntw, int wc, int n_groups, int rec_dwords, kvtc_dtype dtype);
+int encode_lds_bytes(int ntw, int wc, int nw, int n_groups, int rec_dwords, kvtc_dtype dtype);
 int decode_rec_bytes(int tt, int rec_dwords);
 int decode_ring_bytes(int nct);
 int decode_stage_u4(int nct);
@@ -187,13 +187,17 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     d.rec_dwords = (int)((total_bits + 31) / 32);
     const int nt = (r + 31) / 32;
 
-    // encode variant: NTW coordinate tiles per wave, WC waves across coordinates
-    // {waves across coordinates, tiles per wave, wide kernel?}, ascending padded width
-    static const int enc_tab[][3] = {{1, 2, 0}, {1, 4, 0}, {2, 3, 0}, {2, 4, 0}, {2, 5, 0},
-                                     {2, 6, 1}, {2, 8, 1}, {2, 10, 1}, {4, 6, 1}, {4, 8, 1}};
+    // encode variant: NTW coordinate tiles per wave, WC waves across coordinates, NW waves per workgroup
+    // {waves across coordinates, tiles per wave, one workgroup per compute unit?, waves per workgroup}, ascending padded width
+    // Up to 320 padded coordinates a 4-wave workgroup keeps 64 tokens x all its coordinates in 256
+    // registers per lane and two workgroups share a compute unit.  From 321 to 640, 8-wave workgroups
+    // (two waves per SIMD at 256 registers, 128-token tiles, four waves across the coordinates) measured
+    // twice as fast as 4-wave ones with 512 registers; beyond that only the latter hold a tile.
+    static const int enc_tab[][4] = {{1, 2, 0, 4}, {1, 4, 0, 4}, {2, 3, 0, 4}, {2, 4, 0, 4}, {2, 5, 0, 4},
+                                     {4, 3, 1, 8}, {4, 4, 1, 8}, {4, 5, 1, 8}, {4, 6, 1, 4}, {4, 8, 1, 4}};
     d.enc_wc = 0;
     for (auto& e : enc_tab)
-        if (e[0] * e[1] >= nt) { d.enc_wc = e[0]; d.enc_ntw = e[1]; d.enc_wide = e[2]; break; }
+        if (e[0] * e[1] >= nt) { d.enc_wc = e[0]; d.enc_ntw = e[1]; d.enc_wide = e[2]; d.enc_nw = e[3]; break; }
     // {token tiles per wave, coordinate tiles, wide kernel?}
     static const int dec_tab[][3] = {{2, 2, 0}, {2, 4, 0}, {2, 6, 0}, {2, 8, 0}, {2, 10, 0},
                                      {2, 12, 1}, {2, 16, 1}, {2, 20, 1}, {2, 24, 1}, {1, 32, 1}};
@@ -202,11 +206,11 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
         if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; d.dec_wide = e[2]; break; }
     if (d.enc_wc == 0 || d.dec_tt == 0) return fail(KVTC_E_UNSUPPORTED, "kvtc_plan_create: no kernel variant for r=%d", r);
     const int ntp = d.enc_ntw * d.enc_wc;
-    d.enc_tok_wg = 64 * (4 / d.enc_wc);
+    d.enc_tok_wg = 64 * (d.enc_nw / d.enc_wc);
     d.dec_tok_wg = 4 * 32 * d.dec_tt;
     {
-        d.enc_lds[KVTC_BF16] = encode_lds_bytes(d.enc_ntw, d.enc_wc, n_groups, d.rec_dwords, KVTC_BF16);
-        d.enc_lds[KVTC_F32] = encode_lds_bytes(d.enc_ntw, d.enc_wc, n_groups, d.rec_dwords, KVTC_F32);
+        d.enc_lds[KVTC_BF16] = encode_lds_bytes(d.enc_ntw, d.enc_wc, d.enc_nw, n_groups, d.rec_dwords, KVTC_BF16);
+        d.enc_lds[KVTC_F32] = encode_lds_bytes(d.enc_ntw, d.enc_wc, d.enc_nw, n_groups, d.rec_dwords, KVTC_F32);
         d.dec_rec_lds = decode_rec_bytes(d.dec_tt, d.rec_dwords);
         d.dec_ring_lds = decode_ring_bytes(d.dec_nct);
     }
@@ -373,7 +377,7 @@ kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dty
     const int64_t tiles = (n_tokens + plan->h.enc_tok_wg - 1) / plan->h.enc_tok_wg;
     const int slots = cu_count() * (plan->h.enc_wide ? 1 : 2);
     const int grid = (int)(tiles < slots ? tiles : slots);
-    hipError_t e = launch_encode(a, dtype, plan->h.enc_wc * 100 + plan->h.enc_ntw, grid, (size_t)kJobTableBytes + 64 + plan->h.enc_lds[dtype], static_cast<hipStream_t>(stream));
+    hipError_t e = launch_encode(a, dtype, plan->h.enc_nw * 10000 + plan->h.enc_wc * 100 + plan->h.enc_ntw, grid, (size_t)kJobTableBytes + 64 + plan->h.enc_lds[dtype], static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }
@@ -429,7 +433,7 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
         b->rec_dwords.push_back(plans[i]->h.rec_dwords);
         const PlanDev& ph = plans[i]->h;
         {
-            const int key = ph.enc_wc * 100 + ph.enc_ntw;
+            const int key = ph.enc_nw * 10000 + ph.enc_wc * 100 + ph.enc_ntw;
             kvtc_batch::EncVariant* v = nullptr;
             for (auto& e : b->enc)
                 if (e.key == key) v = &e;

@@ -24,7 +24,8 @@ struct PlanDev {
     int32_t enc_lds[2];                     // encode: dynamic LDS bytes needed (without the job table), per element dtype
     int32_t dec_rec_lds, dec_ring_lds;      // decode: bytes of the record image, of the basis ring + mu
     int32_t code_bits_max;                  // widest code of the plan
-    int32_t enc_wide, dec_wide;             // 0: the variant runs two waves per SIMD (256 registers), 1: one (512)
+    int32_t enc_wide, dec_wide;             // 0: two workgroups per compute unit, 1: one
+    int32_t enc_nw, pad_;                   // encode: waves per workgroup (4 or 8)
     const uint4* v_enc;    // [p/16][32*ntp/32][64] MFMA A fragments of V_kept^T (encode)
     const uint4* v_dec;    // [p/32][2*nct*64 + 16] MFMA B fragments of V_kept^T (decode), then the tile's 32 mu entries; tiles 2k, 2k+1 = even, odd features of span k
     const float* negc;     // [32*ntp]  -(mu^T V_kept), zero in the padding
@@ -58,18 +59,18 @@ struct TileRef {
 // Builds the exclusive prefix of tiles per job in LDS (tile_start[0..n_jobs]) and returns
 // the total.  A job with a bad plan index, a negative token count or a stream that would end
 // beyond `cap` gets zero tiles, and so does a job whose plan belongs to another kernel variant
-// (variant_key: 100 * first + second variant parameter); workgroup 0 reports the lowest bad job in *status.
-template <bool kEncode>
-__device__ inline uint32_t build_tile_table(const KernelArgs& a, int variant_key, uint32_t* tile_start, uint32_t* scratch /*[kThreads + 1]*/) {
+// (variant_key: the variant's parameters in decimal positions); workgroup 0 reports the lowest bad job in *status.
+template <bool kEncode, int NT = kThreads>
+__device__ inline uint32_t build_tile_table(const KernelArgs& a, int variant_key, uint32_t* tile_start, uint32_t* scratch /*[NT + 1]*/) {
     const int tid = threadIdx.x;
     const int n_jobs = a.jobs ? a.n_jobs : 1;
-    const int per = (n_jobs + kThreads - 1) / kThreads;
+    const int per = (n_jobs + NT - 1) / NT;
     const int j0 = tid * per;
-    uint32_t local[kMaxJobs / kThreads];
+    uint32_t local[kMaxJobs / NT];
     uint32_t sum = 0;
     uint32_t first_bad = 0xffffffffu;
 #pragma unroll
-    for (int k = 0; k < kMaxJobs / kThreads; ++k) {
+    for (int k = 0; k < kMaxJobs / NT; ++k) {
         uint32_t tiles = 0;
         const int j = j0 + k;
         if (k < per && j < n_jobs) {
@@ -80,7 +81,7 @@ __device__ inline uint32_t build_tile_table(const KernelArgs& a, int variant_key
                 const PlanDev& pl = a.plans[jb.plan];
                 const int tw = kEncode ? pl.enc_tok_wg : pl.dec_tok_wg;
                 // each launch serves the plans of its own kernel variant; other launches take the rest
-                if ((kEncode ? pl.enc_wc * 100 + pl.enc_ntw : pl.dec_tt * 100 + pl.dec_nct) == variant_key)
+                if ((kEncode ? pl.enc_nw * 10000 + pl.enc_wc * 100 + pl.enc_ntw : pl.dec_tt * 100 + pl.dec_nct) == variant_key)
                     tiles = (uint32_t)((jb.n_tokens + tw - 1) / tw);
             } else if (first_bad == 0xffffffffu) {
                 first_bad = (uint32_t)j;
@@ -92,16 +93,16 @@ __device__ inline uint32_t build_tile_table(const KernelArgs& a, int variant_key
     // exclusive scan of the per-thread sums
     scratch[tid] = sum;
     __syncthreads();
-    for (int d = 1; d < kThreads; d <<= 1) {
+    for (int d = 1; d < NT; d <<= 1) {
         uint32_t v = tid >= d ? scratch[tid - d] : 0u;
         __syncthreads();
         scratch[tid] += v;
         __syncthreads();
     }
     uint32_t run = scratch[tid] - sum;
-    const uint32_t total = scratch[kThreads - 1];
+    const uint32_t total = scratch[NT - 1];
 #pragma unroll
-    for (int k = 0; k < kMaxJobs / kThreads; ++k) {
+    for (int k = 0; k < kMaxJobs / NT; ++k) {
         const int j = j0 + k;
         if (k < per && j < n_jobs) tile_start[j] = run;
         run += local[k];
@@ -112,7 +113,7 @@ __device__ inline uint32_t build_tile_table(const KernelArgs& a, int variant_key
     if (a.status && blockIdx.x == 0) {
         scratch[tid] = first_bad;
         __syncthreads();
-        for (int d = kThreads / 2; d > 0; d >>= 1) {
+        for (int d = NT / 2; d > 0; d >>= 1) {
             if (tid < d) scratch[tid] = min(scratch[tid], scratch[tid + d]);
             __syncthreads();
         }

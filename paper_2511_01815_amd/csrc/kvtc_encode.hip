@@ -69,8 +69,17 @@ __device__ __forceinline__ void put_bits(uint32_t* rec, uint32_t pos, uint32_t v
 // k-steps (16 features each) per pipeline stage, and stages in the LDS ring.  Sized so that a
 // narrow plan (<= 10 coordinate tiles, two workgroups per compute unit) stays within ~72 KB
 // and a wide one (one workgroup) within ~150 KB.
-__host__ __device__ constexpr int enc_ks(int ntp) { return ntp <= 8 || (ntp > 10 && ntp <= 16) ? 2 : 1; }
-__host__ __device__ constexpr int enc_stages(int ntp) { return enc_ks(ntp) == 2 ? 3 : 4; }
+__host__ __device__ constexpr int enc_ks(int ntp, int elem_bytes) {
+    return ntp <= 8 || (ntp > 10 && ntp <= (elem_bytes == 2 ? 20 : 16)) ? 2 : 1;      // fp32 X slabs are twice as large
+}
+// stages: as many as fit the variant's LDS share (two workgroups per compute unit: ~72 KB, one: ~150 KB), 2..4
+__host__ __device__ constexpr int enc_stages(int ntp, int elem_bytes, int nw, int wc) {
+    const int ks = enc_ks(ntp, elem_bytes);
+    const int stage_b = ks * ntp * 1024 + 64 * (nw / wc) * ks * 16 * elem_bytes;
+    const int budget = (nw == 4 && ntp <= 10 ? 72 : 150) * 1024;
+    const int n = budget / stage_b;
+    return n < 2 ? 2 : (n > 4 ? 4 : n);
+}
 
 // LDS work area (behind the job table): [tables of the tile's plan: block table 64 dwords, group
 // table 64 dwords, -(mu^T V_kept) of the padded coordinates][ring / epilogue images].  The tables
@@ -80,18 +89,19 @@ __host__ __device__ constexpr int enc_stages(int ntp) { return enc_ks(ntp) == 2 
 constexpr int kEncBlkOff = 0, kEncGrpOff = 256, kEncNegcOff = 512;
 __host__ __device__ constexpr int enc_aux_bytes(int ntp) { return 512 + ntp * 32 * 4; }
 
-template <int NTW, int WC, typename XT>
+template <int NTW, int WC, typename XT, int NW>
 __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
                                             const KernelArgs& a, uint4* work) {
     constexpr int TT = 2;                    // token tiles (of 32) per wave
     constexpr int NTP = NTW * WC;            // coordinate tiles of the padded plan
-    constexpr int WT = 4 / WC;               // waves across tokens
+    constexpr int NTH = NW * 64;             // threads of the workgroup
+    constexpr int WT = NW / WC;              // waves across tokens
     constexpr int TOK_WG = 64 * WT;
-    constexpr int KS = enc_ks(NTP);
-    constexpr int NSTAGE = enc_stages(NTP);
+    constexpr int KS = enc_ks(NTP, (int)sizeof(XT));
+    constexpr int NSTAGE = enc_stages(NTP, (int)sizeof(XT), NW, WC);
     constexpr int SLAB_U4 = KS * NTP * 64;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wc = wave % WC, wt = wave / WC;
     const int l32 = lane & 31, h = lane >> 5;
     const int p = P.p;
@@ -104,7 +114,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
         const uint32_t aux = lds_offset(work);
         if (wave == 0) dma4_async(P.blk, (uint32_t)lane * 4u, aux + kEncBlkOff);
         if (wave == 1) dma4_async(P.grp, (uint32_t)lane * 4u, aux + kEncGrpOff);       // 64 entries allocated
-        static_assert(NTP * 8 <= kThreads, "one 16-byte piece per thread covers -(mu^T V_kept)");
+        static_assert(NTP * 8 <= NTH, "one 16-byte piece per thread covers -(mu^T V_kept)");
         if (wave * 64 < NTP * 8 && tid < NTP * 8)
             dma16_async(P.negc, (uint32_t)tid * 16u, aux + kEncNegcOff + (uint32_t)wave * 1024u);
     }
@@ -116,10 +126,10 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
     constexpr int XSLAB_B = TOK_WG * XS::ROW_B;
     constexpr int STAGE_B = SLAB_U4 * 16 + XSLAB_B;
     constexpr int NX_TOTAL = TOK_WG / XS::ROWS_PER_DMA;         // X transfers per stage, dealt round-robin to the waves
-    constexpr int NXD = (NX_TOTAL + 3) / 4;
+    constexpr int NXD = (NX_TOTAL + NW - 1) / NW;
     constexpr int NV_TOTAL = SLAB_U4 / 64;                      // basis transfers per stage (1 KB each), dealt the same way
-    constexpr int NV = (NV_TOTAL + 3) / 4;
-    constexpr int NDMA_MIN = NV_TOTAL / 4 + NX_TOTAL / 4;       // transfers per wave per stage, lower bound over waves
+    constexpr int NV = (NV_TOTAL + NW - 1) / NW;
+    constexpr int NDMA_MIN = NV_TOTAL / NW + NX_TOTAL / NW;     // transfers per wave per stage, lower bound over waves
     static_assert(TOK_WG % XS::ROWS_PER_DMA == 0, "whole transfers");
     static_assert(3 * (NV + NXD) < 64, "vmcnt range");
     char* ring = reinterpret_cast<char*>(smem);
@@ -131,7 +141,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
     uint32_t xdst[NXD];                                         // wave-uniform LDS byte offsets inside an X slab
 #pragma unroll
     for (int j = 0; j < NXD; ++j) {
-        const int row0 = (j * 4 + wave) * XS::ROWS_PER_DMA;
+        const int row0 = (j * NW + wave) * XS::ROWS_PER_DMA;
         const int row = row0 + lane / XS::COLS;
         const int col = (lane % XS::COLS) ^ XS::swz(row);
         int t = tok_tile0 + row;
@@ -149,11 +159,11 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
         const uint4* vsrc = vg + (size_t)s * SLAB_U4 + wave * 64 + lane;
 #pragma unroll
         for (int i = 0; i < NV; ++i)
-            if (i * 4 + wave < NV_TOTAL)
-                dma16_async(vsrc + i * kThreads, __builtin_amdgcn_readfirstlane(base + (i * kThreads + wave * 64) * 16));
+            if (i * NW + wave < NV_TOTAL)
+                dma16_async(vsrc + i * NTH, __builtin_amdgcn_readfirstlane(base + (i * NTH + wave * 64) * 16));
 #pragma unroll
         for (int j = 0; j < NXD; ++j)
-            if (j * 4 + wave < NX_TOTAL)
+            if (j * NW + wave < NX_TOTAL)
                 dma16_async(xsrc[j] + (size_t)s * XS::ROW_B, __builtin_amdgcn_readfirstlane(base + xdst[j]));
     };
     auto compute = [&](int stage) {
@@ -242,11 +252,11 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
             __builtin_amdgcn_sched_barrier(0);      // keep the accumulator reads from piling up
         }
     }
-    for (int i = tid; i < TOK_WG * rstride; i += kThreads) rec[i] = 0u;
+    for (int i = tid; i < TOK_WG * rstride; i += NTH) rec[i] = 0u;
     __syncthreads();
 
     // B: one header per (token, group)
-    for (int item = tid; item < TOK_WG * G; item += kThreads) {
+    for (int item = tid; item < TOK_WG * G; item += NTH) {
         const int tw = item % TOK_WG, g = item / TOK_WG;
         const uint32_t gi = grp_t[g];
         const int b0 = gi & 0xff, nb = (gi >> 8) & 0xff, bits = (gi >> 16) & 0xff;
@@ -311,7 +321,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
                         (size_t)tok_tile0 * rd;
         const uint32_t magic = 0xffffffffu / (uint32_t)rd + 1u;     // exact floor(i / rd) for i < 2^20
         const int total = n_valid * rd;
-        for (int i = tid; i < total; i += kThreads) {
+        for (int i = tid; i < total; i += NTH) {
             const uint32_t t = __umulhi((uint32_t)i, magic);
             out[i] = rec[t * rstride + ((uint32_t)i - t * rd)];
         }
@@ -319,35 +329,40 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
     __syncthreads();
 }
 
-// One kernel per variant (WC waves across coordinates, NTW coordinate tiles per wave): plans of up
-// to 320 padded coordinates fit in 256 registers per lane and run two workgroups per compute unit
-// (one hides the other's memory waits and epilogue); wider plans get the whole register file.  A
-// batched launch serves only the jobs whose plan uses its variant.
-template <int WC, int NTW> constexpr int enc_wgs_per_cu() { return WC * NTW <= 10 ? 2 : 1; }
+// One kernel per variant (WC waves across coordinates, NTW coordinate tiles per wave, NW waves per
+// workgroup): plans of up to 320 padded coordinates fit 4-wave workgroups with 256 registers per lane,
+// two per compute unit (one hides the other's memory waits and epilogue); wider plans get the compute
+// unit to themselves, as 8 waves of 256 registers or 4 of 512.  A batched launch serves only the jobs
+// whose plan uses its variant.
+template <int WC, int NTW, int NW> constexpr int enc_wgs_per_cu() { return NW == 4 && WC * NTW <= 10 ? 2 : 1; }
 
-template <typename XT, int WC, int NTW>
-__global__ void __launch_bounds__(kThreads, (enc_wgs_per_cu<WC, NTW>())) kvtc_encode_kernel(const KernelArgs a) {
+template <typename XT, int WC, int NTW, int NW>
+__global__ void __launch_bounds__(NW * 64, (enc_wgs_per_cu<WC, NTW, NW>())) kvtc_encode_kernel(const KernelArgs a) {
     extern __shared__ uint4 smem[];
     uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
     uint4* work = smem + kJobTableBytes / 16 + 1;
-    const uint32_t total = build_tile_table<true>(a, WC * 100 + NTW, tile_start, reinterpret_cast<uint32_t*>(work));
+    const uint32_t total = build_tile_table<true, NW * 64>(a, NW * 10000 + WC * 100 + NTW, tile_start, reinterpret_cast<uint32_t*>(work));
     for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
         const TileRef tr = find_tile(a, tile_start, tile);
         const PlanEnc P = load_plan_enc(a.plans + tr.plan);
-        encode_tile<NTW, WC, XT>(P, tr, a, work);
+        encode_tile<NTW, WC, XT, NW>(P, tr, a, work);
     }
 }
 
-#define KVTC_ENC_VARIANTS(X) X(1, 2) X(1, 4) X(2, 3) X(2, 4) X(2, 5) X(2, 6) X(2, 8) X(2, 10) X(4, 6) X(4, 8)
+// (waves across coordinates, coordinate tiles per wave, waves per workgroup)
+#define KVTC_ENC_VARIANTS(X)                                                                           \
+    X(1, 2, 4) X(1, 4, 4) X(2, 3, 4) X(2, 4, 4) X(2, 5, 4) X(4, 3, 8) X(4, 4, 8) X(4, 5, 8) X(4, 6, 4) X(4, 8, 4)
 
-// key = 100 * WC + NTW
+// key = 10000 * NW + 100 * WC + NTW
 hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream) {
     const void* fn = nullptr;
+    int threads = 0;
     switch (key) {
-#define KVTC_X(WC, NTW)                                                                                        \
-    case (WC) * 100 + (NTW):                                                                                   \
-        fn = dtype == KVTC_BF16 ? reinterpret_cast<const void*>(&kvtc_encode_kernel<uint16_t, WC, NTW>)        \
-                                : reinterpret_cast<const void*>(&kvtc_encode_kernel<float, WC, NTW>);          \
+#define KVTC_X(WC, NTW, NW)                                                                                    \
+    case (NW) * 10000 + (WC) * 100 + (NTW):                                                                    \
+        fn = dtype == KVTC_BF16 ? reinterpret_cast<const void*>(&kvtc_encode_kernel<uint16_t, WC, NTW, NW>)    \
+                                : reinterpret_cast<const void*>(&kvtc_encode_kernel<float, WC, NTW, NW>);      \
+        threads = (NW) * 64;                                                                                   \
         break;
         KVTC_ENC_VARIANTS(KVTC_X)
 #undef KVTC_X
@@ -357,15 +372,16 @@ hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int gri
     if (e != hipSuccess) return e;
     KernelArgs args = a;
     void* params[] = {&args};
-    return hipLaunchKernel(fn, dim3(grid), dim3(kThreads), params, lds_bytes, stream);
+    return hipLaunchKernel(fn, dim3(grid), dim3(threads), params, lds_bytes, stream);
 }
 
 // LDS bytes encode_tile needs for a variant (main loop slabs vs epilogue images).
-int encode_lds_bytes(int ntw, int wc, int n_groups, int rec_dwords, kvtc_dtype dtype) {
+int encode_lds_bytes(int ntw, int wc, int nw, int n_groups, int rec_dwords, kvtc_dtype dtype) {
     const int ntp = ntw * wc;
-    const int ks = enc_ks(ntp);
-    const int tok_wg = 64 * (4 / wc);
-    const int main_b = enc_stages(ntp) * (ks * ntp * 1024 + tok_wg * ks * (dtype == KVTC_BF16 ? 32 : 64));
+    const int eb = dtype == KVTC_BF16 ? 2 : 4;
+    const int ks = enc_ks(ntp, eb);
+    const int tok_wg = 64 * (nw / wc);
+    const int main_b = enc_stages(ntp, eb, nw, wc) * (ks * ntp * 1024 + tok_wg * ks * (dtype == KVTC_BF16 ? 32 : 64));
     const int epi_b = tok_wg * (2 * ntp * 8 + n_groups * 8 + (rec_dwords + 1) * 4);
     return enc_aux_bytes(ntp) + (main_b > epi_b ? main_b : epi_b);
 }
