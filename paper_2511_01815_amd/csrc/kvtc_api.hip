@@ -200,7 +200,7 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
         if (e[0] * e[1] >= nt) { d.enc_wc = e[0]; d.enc_ntw = e[1]; d.enc_wide = e[2]; d.enc_nw = e[3]; break; }
     // {token tiles per wave, coordinate tiles, wide kernel?}
     static const int dec_tab[][3] = {{2, 2, 0}, {2, 4, 0}, {2, 6, 0}, {2, 8, 0}, {2, 10, 0},
-                                     {2, 12, 1}, {2, 16, 1}, {2, 20, 1}, {2, 24, 1}, {1, 32, 1}};
+                                     {2, 12, 1}, {2, 16, 1}, {2, 18, 1}, {2, 20, 1}, {2, 24, 1}, {1, 32, 1}};
     d.dec_tt = 0;
     for (auto& e : dec_tab)
         if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; d.dec_wide = e[2]; break; }

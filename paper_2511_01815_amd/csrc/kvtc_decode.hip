@@ -323,7 +323,7 @@ __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, NCT>())) kvtc_de
     }
 }
 
-#define KVTC_DEC_VARIANTS(X) X(2, 2) X(2, 4) X(2, 6) X(2, 8) X(2, 10) X(2, 12) X(2, 16) X(2, 20) X(2, 24) X(1, 32)
+#define KVTC_DEC_VARIANTS(X) X(2, 2) X(2, 4) X(2, 6) X(2, 8) X(2, 10) X(2, 12) X(2, 16) X(2, 18) X(2, 20) X(2, 24) X(1, 32)
 
 // key = 100 * TT + NCT
 hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream) {
