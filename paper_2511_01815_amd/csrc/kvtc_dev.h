@@ -231,31 +231,17 @@ __device__ inline TileRef find_tile(const KernelArgs& a, const uint32_t* tile_st
     return t;
 }
 
-// 16 bytes per lane from global memory straight into LDS, no register staging: lane i's
-// bytes land at lds_wave_base + 16 * i (lds_wave_base must be wave-uniform).
-__device__ __forceinline__ void dma16(const uint4* gsrc, uint4* lds_wave_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
-                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
-}
-
-// Copy n_u4 (a multiple of 256) uint4 from global to LDS with the whole workgroup.
-template <int N_U4>
-__device__ __forceinline__ void dma_slab(const uint4* __restrict__ src, uint4* dst, int wave, int lane) {
-    static_assert(N_U4 % kThreads == 0, "whole rounds of the workgroup");
-#pragma unroll
-    for (int i = 0; i < N_U4 / kThreads; ++i)
-        dma16(src + i * kThreads + wave * 64 + lane, dst + i * kThreads + wave * 64);
-}
-
 // LDS byte offset of a pointer into shared memory.
 __device__ __forceinline__ uint32_t lds_offset(const void* p) {
     return (uint32_t)(size_t)(const __attribute__((address_space(3))) void*)p;
 }
 
-// The same transfer issued behind the compiler's back: it neither orders later LDS reads after
-// it nor counts it, so a step's transfers can stay in flight while the previous slab is read.
-// The caller owns the wait: wait_vmem_all() before the barrier that publishes the data.
-// lds_byte_addr must be wave-uniform (it goes through M0).
+// 16 bytes per lane from global memory straight into LDS, no register staging: lane i's bytes
+// land at lds_byte_addr + 16 * i (wave-uniform address; it goes through M0).  Issued behind the
+// compiler's back: the compiler neither orders later LDS reads after it nor counts it, so a
+// step's transfers can stay in flight while the previous slab is read (the builtin form makes the
+// compiler wait for vmcnt(0) before any later LDS read).  The caller owns the wait: wait_vmem<N>()
+// before the barrier that publishes the data.
 __device__ __forceinline__ void dma16_async(const void* gsrc, uint32_t lds_byte_addr) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :: "v"(gsrc), "s"(lds_byte_addr) : "memory");
@@ -283,7 +269,6 @@ template <int N> __device__ __forceinline__ void wait_vmem() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
-__device__ __forceinline__ void wait_vmem_all() { wait_vmem<0>(); }
 // s_waitcnt vmcnt(n) with a wave-uniform run-time n; n above 63 waits as for 63.
 __device__ __forceinline__ void wait_vmem_dyn(int n) {
 #define KVTC_W(N) case N: wait_vmem<N>(); break;

@@ -290,6 +290,12 @@ def test_degenerate_inputs(c1):
     with pytest.raises(kv.KvtcError) as e:
         kv.kvtc_encode(plan.handle, x.view(torch.uint8).flatten()[2:].data_ptr(), kv.KVTC_BF16, 1, p, buf, 1 << 20)
     assert e.value.status == 1
+    with pytest.raises(kv.KvtcError) as e:          # row pitch above the documented limit
+        kv.kvtc_encode(plan.handle, x, kv.KVTC_BF16, 1, (1 << 21) + 8, buf, 1 << 20)
+    assert e.value.status == 1
+    with pytest.raises(kv.KvtcError) as e:
+        kv.kvtc_decode(plan.handle, buf, 64, 1, x, kv.KVTC_BF16, (1 << 21) + 8)
+    assert e.value.status == 1
     torch.cuda.synchronize()
 
 
