@@ -76,7 +76,7 @@ typedef struct { int32_t plan; int32_t n_tokens; int64_t x_row0; } kvtc_job;
  * mean mu, basis V trimmed to the coordinates with non-zero width, and the
  * per-group widths and sizes).
  *   p            features per token; multiple of 64
- *   r            kept coordinates, 16 <= r <= 1024, r <= 1024
+ *   r            kept coordinates, 16 <= r <= 1024
  *   mu_host      [p] fp32
  *   v_kept_host  [p][r] row-major bf16 bit patterns (column j = j-th kept coordinate)
  *   groups_host  n_groups kept groups in PCA order; sum of n must equal r
@@ -97,7 +97,8 @@ size_t kvtc_encoded_bytes(const kvtc_plan* plan, int64_t n_tokens);       /* n_t
 /*
  * Encode one tensor (paper, "Compression": project, quantise, pack).
  *   x_dev     [n_tokens][ld_x] elements of `dtype`, row-major, p <= ld_x <= 2^21, 16-byte
- *             aligned base and row pitch (a larger pitch is KVTC_E_ARG).  fp32 inputs are rounded to bf16 (nearest even) on load.
+ *             aligned base and row pitch (a larger pitch is KVTC_E_ARG).  fp32 inputs are
+ *             rounded to bf16 (nearest even) on load.
  *   out_dev   receives n_tokens records; 16-byte aligned; out_cap >= n_tokens * R else
  *             KVTC_E_SMALL and nothing is written.
  * n_tokens == 0 is KVTC_OK and does nothing.
@@ -109,6 +110,9 @@ kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dty
 /*
  * Decode one tensor (paper, "Decompression": unpack, dequantise, back-project, add mu).
  *   in_dev    n_tokens records, 16-byte aligned; in_bytes >= n_tokens * R else KVTC_E_SMALL.
+ *             The kernel fetches the stream in aligned 16-byte pieces, so when a tensor's
+ *             records do not end on a 16-byte boundary it also reads the rest of that last
+ *             16-byte block (never beyond it; the bytes are ignored).
  *   x_out_dev [n_tokens][ld_x] of `dtype`; results are rounded to nearest even for bf16.
  */
 kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_bytes,
@@ -117,7 +121,8 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
 
 /*
  * Batched / ragged calls: many tensors (jobs), each with its own plan and length, in
- * one launch per direction.  A kvtc_batch makes the plans' descriptors addressable
+ * one launch per direction and per kernel variant among the batch's plans (plans of
+ * similar rank share a variant: usually one launch).  A kvtc_batch makes the plans' descriptors addressable
  * from the device; it copies what it needs, but the plans must outlive it.
  * At most 1024 jobs per call (KVTC_E_UNSUPPORTED beyond).
  */
