@@ -177,7 +177,7 @@ __device__ __forceinline__ PlanDec load_plan_dec(const PlanDev* P) {
 
 // The fields of a plan descriptor the encode kernel uses, in scalar registers.
 struct PlanEnc {
-    int32_t p, n_groups, rec_dwords, enc_ntw, enc_wc;
+    int32_t p, n_groups, rec_dwords, enc_ntw, enc_wc, code_bits_max;
     const uint4* v_enc;
     const float* negc;
     const uint32_t* blk;
@@ -186,8 +186,9 @@ struct PlanEnc {
 __device__ __forceinline__ PlanEnc load_plan_enc(const PlanDev* P) {
     static_assert(offsetof(PlanDev, n_groups) == 8 && offsetof(PlanDev, enc_ntw) == 20 && offsetof(PlanDev, enc_wc) == 24, "descriptor layout");
     const char* b = reinterpret_cast<const char*>(P);
-    const u32x4 q0 = sload_x4(b), q1 = sload_x4(b + 16);
+    const u32x4 q0 = sload_x4(b), q1 = sload_x4(b + 16), q3 = sload_x4(b + 48);
     PlanEnc d;
+    d.code_bits_max = (int32_t)q3[3];
     d.p = (int32_t)q0[0];
     d.n_groups = (int32_t)q0[2];
     d.rec_dwords = (int32_t)q1[0];

@@ -66,6 +66,26 @@ __device__ __forceinline__ void put_bits(uint32_t* rec, uint32_t pos, uint32_t v
     if (s + len > 32u) atomicOr(rec + dw + 1, v >> (32u - s));
 }
 
+// The 16 codes of a block, BITS wide each, as a bit string of BITS halfwords written to the record
+// image at a halfword address (blocks start and end on halfword boundaries: 16 codes x BITS bits).
+// Plain 16-bit LDS stores: two blocks may share a dword but never a halfword, so nothing is OR-ed
+// and the image needs no clearing.
+template <int BITS>
+__device__ __forceinline__ void emit_block(const uint32_t (&c)[16], char* dst) {
+    uint32_t q[(BITS + 1) / 2];
+#pragma unroll
+    for (int j = 0; j < (BITS + 1) / 2; ++j) q[j] = 0u;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int pos = i * BITS, dw = pos >> 5, sh = pos & 31;
+        q[dw] |= c[i] << sh;
+        if (sh + BITS > 32) q[dw + 1] |= c[i] >> (32 - sh);
+    }
+#pragma unroll
+    for (int j = 0; j < BITS; ++j)
+        *reinterpret_cast<uint16_t*>(dst + 2 * j) = (uint16_t)(q[j >> 1] >> (16 * (j & 1)));
+}
+
 // k-steps (16 features each) per pipeline stage, and stages in the LDS ring.  Sized so that a
 // narrow plan (<= 10 coordinate tiles, two workgroups per compute unit) stays within ~72 KB
 // and a wide one (one workgroup) within ~150 KB.
@@ -238,7 +258,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
     float2* gq = mm + 2 * NTP * TOK_WG;
     uint32_t* rec = reinterpret_cast<uint32_t*>(gq + G * TOK_WG);
 
-    // A: block min/max, and clear the record image
+    // A: block min/max
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         const int tw = wt * 64 + tt * 32 + l32;
@@ -252,7 +272,10 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
             __builtin_amdgcn_sched_barrier(0);      // keep the accumulator reads from piling up
         }
     }
-    for (int i = tid; i < TOK_WG * rstride; i += NTH) rec[i] = 0u;
+    // codes wider than 8 bits are OR-ed into the image (cleared here); the usual widths are stored
+    const bool narrow_codes = P.code_bits_max <= 8;
+    if (!narrow_codes)
+        for (int i = tid; i < TOK_WG * rstride; i += NTH) rec[i] = 0u;
     __syncthreads();
 
     // B: one header per (token, group)
@@ -269,6 +292,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
         const GroupQ q = group_header(lo, hi, bits);
         gq[g * TOK_WG + tw] = make_float2(q.shift, q.inv);
         rec[tw * rstride + g] = (uint32_t)q.shift16 | ((uint32_t)q.scale16 << 16);
+        if (g == 0 && narrow_codes) rec[tw * rstride + rd - 1] = 0u;      // the padding behind the last block
     }
     __syncthreads();
 
@@ -294,7 +318,19 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
                     q = __builtin_amdgcn_fmed3f(__builtin_rintf(q), 0.0f, qmax);
                     c[i] = (uint32_t)q;
                 }
-                if (bits <= 8u) {
+                if (narrow_codes) {
+                    char* dst = reinterpret_cast<char*>(row) + (pos0 >> 3);
+                    switch (bits) {
+                        case 1: emit_block<1>(c, dst); break;
+                        case 2: emit_block<2>(c, dst); break;
+                        case 3: emit_block<3>(c, dst); break;
+                        case 4: emit_block<4>(c, dst); break;
+                        case 5: emit_block<5>(c, dst); break;
+                        case 6: emit_block<6>(c, dst); break;
+                        case 7: emit_block<7>(c, dst); break;
+                        default: emit_block<8>(c, dst); break;
+                    }
+                } else if (bits <= 8u) {
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         const uint32_t v = c[4 * k] | (c[4 * k + 1] << bits) | (c[4 * k + 2] << (2u * bits)) |
