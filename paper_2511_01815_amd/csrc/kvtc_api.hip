@@ -35,8 +35,8 @@ struct kvtc_batch {
     PlanDev* plans_dev;
     int n_plans;
     // the kernel variants the plans use (a launch per variant), with the LDS maxima over each one's plans
-    struct EncVariant { int key, wide, lds[2]; };       // lds per element dtype
-    struct DecVariant { int key, wide, rec, ring; };    // record image, basis ring
+    struct EncVariant { int key, wgs, lds[2]; };        // workgroups per compute unit; lds per element dtype
+    struct DecVariant { int key, wgs, rec, ring; };     // workgroups per compute unit; record image, basis ring
     std::vector<EncVariant> enc;
     std::vector<DecVariant> dec;
     int max_p;
@@ -119,11 +119,11 @@ __global__ void __launch_bounds__(256) offsets_kernel(const uint32_t* rec_dwords
 }
 
 // Decode LDS layout for one launch: record image and basis ring side by side when both fit (narrow
-// kernel: within half a compute unit's LDS, so that two workgroups stay resident), which lets each
+// variants: within their share of a compute unit's LDS, so that all their workgroups stay resident), which lets each
 // tile's records be fetched during the previous tile's sweep; otherwise they share the space.
 struct DecLayout { uint32_t ring_off; size_t lds_bytes; };
-DecLayout decode_layout(int rec_b, int ring_b, int wide) {
-    const int budget = (wide ? kLdsBudget : kLdsBudget / 2) - kJobTableBytes - 64;
+DecLayout decode_layout(int rec_b, int ring_b, int wgs_per_cu) {
+    const int budget = kLdsBudget / wgs_per_cu - kJobTableBytes - 64;
     if (rec_b + ring_b <= budget) return {(uint32_t)rec_b, (size_t)kJobTableBytes + 64 + rec_b + ring_b};
     return {0u, (size_t)kJobTableBytes + 64 + (rec_b > ring_b ? rec_b : ring_b)};
 }
@@ -190,20 +190,22 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     // encode variant: NTW coordinate tiles per wave, WC waves across coordinates, NW waves per workgroup
     // {waves across coordinates, tiles per wave, one workgroup per compute unit?, waves per workgroup}, ascending padded width
     // Up to 320 padded coordinates a 4-wave workgroup keeps 64 tokens x all its coordinates in 256
-    // registers per lane and two workgroups share a compute unit.  From 321 to 640, 8-wave workgroups
-    // (two waves per SIMD at 256 registers, 128-token tiles, four waves across the coordinates) measured
-    // twice as fast as 4-wave ones with 512 registers; beyond that only the latter hold a tile.
-    static const int enc_tab[][4] = {{1, 2, 0, 4}, {1, 4, 0, 4}, {2, 3, 0, 4}, {2, 4, 0, 4}, {2, 5, 0, 4},
+    // registers per lane and two workgroups share a compute unit (three where 168 registers suffice:
+    // measured 5 % faster on the 6-tile encode).  From 321 to 640, 8-wave workgroups (two waves per
+    // SIMD at 256 registers, 128-token tiles, four waves across the coordinates) measured twice as fast
+    // as 4-wave ones with 512 registers; beyond that only the latter hold a tile.
+    // {waves across coordinates, tiles per wave, workgroups per compute unit, waves per workgroup}
+    static const int enc_tab[][4] = {{1, 2, 2, 4}, {1, 4, 2, 4}, {2, 3, 3, 4}, {2, 4, 2, 4}, {2, 5, 2, 4},
                                      {4, 3, 1, 8}, {4, 4, 1, 8}, {4, 5, 1, 8}, {4, 6, 1, 4}, {4, 8, 1, 4}};
     d.enc_wc = 0;
     for (auto& e : enc_tab)
-        if (e[0] * e[1] >= nt) { d.enc_wc = e[0]; d.enc_ntw = e[1]; d.enc_wide = e[2]; d.enc_nw = e[3]; break; }
-    // {token tiles per wave, coordinate tiles, wide kernel?}
-    static const int dec_tab[][3] = {{2, 2, 0}, {2, 4, 0}, {2, 6, 0}, {2, 8, 0}, {2, 10, 0},
+        if (e[0] * e[1] >= nt) { d.enc_wc = e[0]; d.enc_ntw = e[1]; d.enc_wgs = e[2]; d.enc_nw = e[3]; break; }
+    // {token tiles per wave, coordinate tiles, workgroups per compute unit}
+    static const int dec_tab[][3] = {{2, 2, 3}, {2, 4, 3}, {2, 6, 2}, {2, 8, 2}, {2, 10, 2},
                                      {2, 12, 1}, {2, 16, 1}, {2, 18, 1}, {2, 20, 1}, {2, 24, 1}, {1, 32, 1}};
     d.dec_tt = 0;
     for (auto& e : dec_tab)
-        if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; d.dec_wide = e[2]; break; }
+        if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; d.dec_wgs = e[2]; break; }
     if (d.enc_wc == 0 || d.dec_tt == 0) return fail(KVTC_E_UNSUPPORTED, "kvtc_plan_create: no kernel variant for r=%d", r);
     const int ntp = d.enc_ntw * d.enc_wc;
     d.enc_tok_wg = 64 * (d.enc_nw / d.enc_wc);
@@ -375,7 +377,7 @@ kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dty
     a.cap = out_cap;
     a.status = nullptr;
     const int64_t tiles = (n_tokens + plan->h.enc_tok_wg - 1) / plan->h.enc_tok_wg;
-    const int slots = cu_count() * (plan->h.enc_wide ? 1 : 2);
+    const int slots = cu_count() * plan->h.enc_wgs;
     const int grid = (int)(tiles < slots ? tiles : slots);
     hipError_t e = launch_encode(a, dtype, plan->h.enc_nw * 10000 + plan->h.enc_wc * 100 + plan->h.enc_ntw, grid, (size_t)kJobTableBytes + 64 + plan->h.enc_lds[dtype], static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode: launch failed: %s", hipGetErrorString(e));
@@ -404,9 +406,9 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
     a.stream_buf = const_cast<void*>(in_dev);
     a.cap = in_bytes;
     const int64_t tiles = (n_tokens + plan->h.dec_tok_wg - 1) / plan->h.dec_tok_wg;
-    const int slots = cu_count() * (plan->h.dec_wide ? 1 : 2);
+    const int slots = cu_count() * plan->h.dec_wgs;
     const int grid = (int)(tiles < slots ? tiles : slots);
-    const DecLayout lay = decode_layout(plan->h.dec_rec_lds, plan->h.dec_ring_lds, plan->h.dec_wide);
+    const DecLayout lay = decode_layout(plan->h.dec_rec_lds, plan->h.dec_ring_lds, plan->h.dec_wgs);
     a.dec_ring_off = lay.ring_off;
     hipError_t e = launch_decode(a, dtype, plan->h.dec_tt * 100 + plan->h.dec_nct, grid, lay.lds_bytes, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode: launch failed: %s", hipGetErrorString(e));
@@ -438,7 +440,7 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
             for (auto& e : b->enc)
                 if (e.key == key) v = &e;
             if (!v) {
-                b->enc.push_back({key, ph.enc_wide, {0, 0}});
+                b->enc.push_back({key, ph.enc_wgs, {0, 0}});
                 v = &b->enc.back();
             }
             for (int dt = 0; dt < 2; ++dt)
@@ -450,7 +452,7 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
             for (auto& e : b->dec)
                 if (e.key == key) v = &e;
             if (!v) {
-                b->dec.push_back({key, ph.dec_wide, 0, 0});
+                b->dec.push_back({key, ph.dec_wgs, 0, 0});
                 v = &b->dec.back();
             }
             if (ph.dec_rec_lds > v->rec) v->rec = ph.dec_rec_lds;
@@ -538,7 +540,7 @@ kvtc_status kvtc_encode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.status = status_dev;
     if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_encode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
     for (const auto& v : batch->enc) {
-        hipError_t e = launch_encode(a, dtype, v.key, cu_count() * (v.wide ? 1 : 2),
+        hipError_t e = launch_encode(a, dtype, v.key, cu_count() * v.wgs,
                                      (size_t)kJobTableBytes + 64 + v.lds[dtype], static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode_batch: launch failed: %s", hipGetErrorString(e));
     }
@@ -566,9 +568,9 @@ kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.status = status_dev;
     if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_decode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
     for (const auto& v : batch->dec) {
-        const DecLayout lay = decode_layout(v.rec, v.ring, v.wide);
+        const DecLayout lay = decode_layout(v.rec, v.ring, v.wgs);
         a.dec_ring_off = lay.ring_off;
-        hipError_t e = launch_decode(a, dtype, v.key, cu_count() * (v.wide ? 1 : 2), lay.lds_bytes, static_cast<hipStream_t>(stream));
+        hipError_t e = launch_decode(a, dtype, v.key, cu_count() * v.wgs, lay.lds_bytes, static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode_batch: launch failed: %s", hipGetErrorString(e));
     }
     return KVTC_OK;

@@ -284,7 +284,8 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
 // a.dec_ring_off the ring sits behind the record image and each tile's records are fetched during
 // the previous tile's sweep; with offset 0 they share the space and the records are fetched at the
 // tile's start.
-template <int TT, int NCT> constexpr int dec_wgs_per_cu() { return NCT <= 10 ? 2 : 1; }
+// (must agree with the host's variant table)
+template <int TT, int NCT> constexpr int dec_wgs_per_cu() { return NCT <= 4 ? 3 : (NCT <= 10 ? 2 : 1); }
 
 template <typename OT, int TT, int NCT>
 __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, NCT>())) kvtc_decode_kernel(const KernelArgs a) {

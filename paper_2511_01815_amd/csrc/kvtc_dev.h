@@ -24,7 +24,7 @@ struct PlanDev {
     int32_t enc_lds[2];                     // encode: dynamic LDS bytes needed (without the job table), per element dtype
     int32_t dec_rec_lds, dec_ring_lds;      // decode: bytes of the record image, of the basis ring + mu
     int32_t code_bits_max;                  // widest code of the plan
-    int32_t enc_wide, dec_wide;             // 0: two workgroups per compute unit, 1: one
+    int32_t enc_wgs, dec_wgs;               // workgroups per compute unit the variant is built for (1..3)
     int32_t enc_nw, pad_;                   // encode: waves per workgroup (4 or 8)
     const uint4* v_enc;    // [p/16][32*ntp/32][64] MFMA A fragments of V_kept^T (encode)
     const uint4* v_dec;    // [p/32][2*nct*64 + 16] MFMA B fragments of V_kept^T (decode), then the tile's 32 mu entries; tiles 2k, 2k+1 = even, odd features of span k

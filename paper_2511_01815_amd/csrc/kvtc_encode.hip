@@ -92,11 +92,11 @@ __device__ __forceinline__ void emit_block(const uint32_t (&c)[16], char* dst) {
 __host__ __device__ constexpr int enc_ks(int ntp, int elem_bytes) {
     return ntp <= 8 || (ntp > 10 && ntp <= (elem_bytes == 2 ? 20 : 16)) ? 2 : 1;      // fp32 X slabs are twice as large
 }
-// stages: as many as fit the variant's LDS share (two workgroups per compute unit: ~72 KB, one: ~150 KB), 2..4
+// stages: as many as fit the variant's LDS share (three workgroups per compute unit: ~44 KB, two: ~72 KB, one: ~150 KB), 2..4
 __host__ __device__ constexpr int enc_stages(int ntp, int elem_bytes, int nw, int wc) {
     const int ks = enc_ks(ntp, elem_bytes);
     const int stage_b = ks * ntp * 1024 + 64 * (nw / wc) * ks * 16 * elem_bytes;
-    const int budget = (nw == 4 && ntp <= 10 ? 72 : 150) * 1024;
+    const int budget = (nw == 4 && wc == 2 && ntp == 6 ? 44 : (nw == 4 && ntp <= 10 ? 72 : 150)) * 1024;
     const int n = budget / stage_b;
     return n < 2 ? 2 : (n > 4 ? 4 : n);
 }
@@ -370,7 +370,10 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
 // two per compute unit (one hides the other's memory waits and epilogue); wider plans get the compute
 // unit to themselves, as 8 waves of 256 registers or 4 of 512.  A batched launch serves only the jobs
 // whose plan uses its variant.
-template <int WC, int NTW, int NW> constexpr int enc_wgs_per_cu() { return NW == 4 && WC * NTW <= 10 ? 2 : 1; }
+// (must agree with the host's variant table)
+template <int WC, int NTW, int NW> constexpr int enc_wgs_per_cu() {
+    return NW == 4 && WC == 2 && NTW == 3 ? 3 : (NW == 4 && WC * NTW <= 10 ? 2 : 1);
+}
 
 template <typename XT, int WC, int NTW, int NW>
 __global__ void __launch_bounds__(NW * 64, (enc_wgs_per_cu<WC, NTW, NW>())) kvtc_encode_kernel(const KernelArgs a) {
