@@ -29,6 +29,18 @@ def _calibrate(workload, layer, kvi, cr):
     return L, oplan
 
 
+@pytest.fixture(scope="module")
+def c2_plans_16_40():
+    """The committed config-2 K bundles at 16x and 40x as oracle plans."""
+    import os
+    plans_dir = os.path.join(os.path.dirname(kv.__file__), "plans")
+    out = []
+    for name in ("c2_K_cr16", "c2_K_cr40"):
+        z = np.load(os.path.join(plans_dir, name + ".npz"))
+        out.append(ko.plan_from_arrays(z["mu32"], z["v_bits"], z["group_n"], z["group_bits"]))
+    return out
+
+
 def _sample_rows(n, rng, k_random=160):
     """Rows worth checking in a job of n tokens: both ends, both sides of workgroup-tile boundaries (128 and 256
     tokens), random ones."""
@@ -165,3 +177,58 @@ def test_config5_ragged_batch():
     st = _check_jobs(res, oplans, plan_of_job, lens, sorted({0, 1, shortest, longest, len(lens) - 1, 100, 301}),
                      np.random.default_rng(35), "c5", max_rel=0.6)
     print("config 5", len(lens), int(lens.sum()), [o.r for o in oplans], [o.record_bytes for o in oplans], st)
+
+
+def test_maximum_job_count_and_many_plans(c2_plans_16_40):
+    """1024 jobs (the limit of one call) over 16 plan objects of two kernel variants, lengths 0..700 including
+    empty jobs; one more job is refused on the host."""
+    oplans2, = (c2_plans_16_40,)
+    n_plans, n_jobs = 16, 1024
+    oplans = [oplans2[i % 2] for i in range(n_plans)]                 # 16x and 40x plans alternate
+    gplans = [_gpu_plan(o) for o in oplans]
+    batch = kv.Batch(gplans)
+    rng = np.random.default_rng(77)
+    lens = rng.integers(0, 701, size=n_jobs)
+    lens[rng.integers(0, n_jobs, size=40)] = 0
+    lens[[0, 5, n_jobs - 1]] = [1, 257, 129]
+    pidx = rng.integers(0, n_plans, size=n_jobs)
+    L = ks.make_layer(ks.layer_spec("c2", 0, 0))
+    total = int(lens.sum())
+    x = ks.draw_bf16_torch(L, total, 99, DEV)
+    row0 = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int64)
+    jobs = kv.make_jobs([int(i) for i in pidx], [int(n) for n in lens], [int(r) for r in row0])
+    jobs_dev = torch.from_numpy(jobs.view(np.uint8)).to(DEV)
+    offs = torch.zeros(n_jobs + 1, dtype=torch.int64, device=DEV)
+    kv.kvtc_offsets(batch.handle, jobs_dev, n_jobs, offs)
+    want = np.concatenate([[0], np.cumsum([int(n) * oplans[i].record_bytes for n, i in zip(lens, pidx)])])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(offs.cpu().numpy(), want)
+    cap = int(want[-1])
+    stream = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device=DEV)
+    status = torch.zeros(2, dtype=torch.int32, device=DEV)
+    kv.kvtc_encode_batch(batch.handle, jobs_dev, n_jobs, x, kv.KVTC_BF16, 1024, offs, stream, cap, status[0:1])
+    x_hat = torch.zeros_like(x)
+    kv.kvtc_decode_batch(batch.handle, jobs_dev, n_jobs, stream, cap, offs, x_hat, kv.KVTC_BF16, 1024, status[1:2])
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    assert torch.all(stream[cap:] == 0xA5)
+    # every token was decoded: the whole output is close to the input (16x and 40x mixed)
+    a, b = x.float(), x_hat.float()
+    assert float((b - a).norm() / (a - a.mean(0)).norm()) < 0.4
+    xs, hs, ss = None, None, stream.cpu().numpy()
+    for j in [0, 5, 17, 400, 801, n_jobs - 1] + [int(k) for k in np.argsort(lens)[-2:]]:
+        n, o = int(lens[j]), oplans[pidx[j]]
+        if n == 0:
+            continue
+        rec = ss[want[j]:want[j + 1]].reshape(n, -1)
+        xv = ks.bf16_bits_to_f32(x[row0[j]:row0[j] + n].view(torch.int16).cpu().numpy().view(np.uint16))
+        xh = ks.bf16_bits_to_f32(x_hat[row0[j]:row0[j] + n].view(torch.int16).cpu().numpy().view(np.uint16))
+        check_stream(o, xv, rec, f"maxjobs-job{j}")
+        check_recon(o, rec, xh, xv, True, f"maxjobs-job{j}")
+    # one job too many
+    jobs2 = kv.make_jobs([0] * 1025, [1] * 1025, list(range(1025)))
+    jd2 = torch.from_numpy(jobs2.view(np.uint8)).to(DEV)
+    offs2 = torch.zeros(1026, dtype=torch.int64, device=DEV)
+    with pytest.raises(kv.KvtcError) as e:
+        kv.kvtc_encode_batch(batch.handle, jd2, 1025, x, kv.KVTC_BF16, 1024, offs2, stream, cap, status[0:1])
+    assert e.value.status == 2
