@@ -332,3 +332,26 @@ def test_decode_is_a_plain_matrix_product():
     # zero-bit block in the middle is dropped, kept indices need not be a prefix
     plan2 = ko.compile_plan(mu, V, [ko.Block(0, 16, 0), ko.Block(16, 16, 3)])
     assert plan2.kept.tolist() == list(range(16, 32)) and plan2.record_bytes == 12   # 32 + 16*3 = 80 bits -> 3 dwords
+
+
+def test_committed_bundle_is_what_the_calibration_script_writes():
+    """The calibration bundles the benchmark loads are stored values; they must be exactly what the
+    oracle's calibration (PCA + DP allocation at 16x on the seeded config-2 calibration draw) produces,
+    and the hand-set full-rank bundle must keep every coordinate of the same basis."""
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    plans_dir = os.path.join(root, "paper_2511_01815_amd", "plans")
+    wl = ks.WORKLOADS["c2"]
+    L = ks.make_layer(ks.layer_spec("c2", 0, 0))
+    C = ks.bf16_bits_to_f32(ks.draw_bf16(L, wl.n_calib, ks.CALIB_DRAW))
+    mu, V, S = ko.pca(C)
+    plan, info = ko.calibrate_from_pca(C, mu, V, S, 16.0, errors=ko.dp_errors(C, mu, V))
+    z = np.load(os.path.join(plans_dir, "c2_K_cr16.npz"))
+    np.testing.assert_array_equal(z["v_bits"], plan.v_bits)
+    np.testing.assert_array_equal(z["mu32"], plan.mu32)
+    assert z["group_n"].tolist() == plan.group_n.tolist() and z["group_bits"].tolist() == plan.group_bits.tolist()
+    assert plan.record_bytes * 8 <= info["budget_bits"] == 1024
+    full = np.load(os.path.join(plans_dir, "c2_K_full.npz"))
+    assert full["v_bits"].shape == (1024, 1024) and int(full["group_n"].sum()) == 1024
+    np.testing.assert_array_equal(full["v_bits"][:, :16], plan.v_bits[:, :16])      # same leading PCA directions
+    np.testing.assert_array_equal(full["mu32"], plan.mu32)
