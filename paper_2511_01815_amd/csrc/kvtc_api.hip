@@ -17,6 +17,7 @@ namespace kvtc {
 hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream);
 hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream);
 int encode_lds_bytes(int ntw, int wc, int nw, int n_groups, int rec_dwords, kvtc_dtype dtype);
+int encode_tok_wg(int ntw, int wc, int nw);
 int decode_rec_bytes(int tt, int rec_dwords);
 int decode_ring_bytes(int nct);
 int decode_stage_u4(int nct);
@@ -208,7 +209,7 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
         if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; d.dec_wgs = e[2]; break; }
     if (d.enc_wc == 0 || d.dec_tt == 0) return fail(KVTC_E_UNSUPPORTED, "kvtc_plan_create: no kernel variant for r=%d", r);
     const int ntp = d.enc_ntw * d.enc_wc;
-    d.enc_tok_wg = 64 * (d.enc_nw / d.enc_wc);
+    d.enc_tok_wg = encode_tok_wg(d.enc_ntw, d.enc_wc, d.enc_nw);
     d.dec_tok_wg = 4 * 32 * d.dec_tt;
     {
         d.enc_lds[KVTC_BF16] = encode_lds_bytes(d.enc_ntw, d.enc_wc, d.enc_nw, n_groups, d.rec_dwords, KVTC_BF16);

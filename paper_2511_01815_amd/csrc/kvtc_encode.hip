@@ -89,13 +89,16 @@ __device__ __forceinline__ void emit_block(const uint32_t (&c)[16], char* dst) {
 // k-steps (16 features each) per pipeline stage, and stages in the LDS ring.  Sized so that a
 // narrow plan (<= 10 coordinate tiles, two workgroups per compute unit) stays within ~72 KB
 // and a wide one (one workgroup) within ~150 KB.
+// token tiles (of 32) per wave: three where the registers allow it (8 coordinate tiles over two
+// waves: 192 accumulator registers), which cuts the basis traffic per token by a third
+__host__ __device__ constexpr int enc_tt(int ntp, int nw, int wc) { return nw == 4 && wc == 2 && ntp == 8 ? 3 : 2; }
 __host__ __device__ constexpr int enc_ks(int ntp, int elem_bytes) {
-    return ntp <= 8 || (ntp > 10 && ntp <= (elem_bytes == 2 ? 20 : 16)) ? 2 : 1;      // fp32 X slabs are twice as large
+    return ntp < 8 || (ntp == 8 && elem_bytes == 2) || (ntp > 10 && ntp <= (elem_bytes == 2 ? 20 : 16)) ? 2 : 1;      // fp32 X slabs are twice as large
 }
 // stages: as many as fit the variant's LDS share (three workgroups per compute unit: ~44 KB, two: ~72 KB, one: ~150 KB), 2..4
 __host__ __device__ constexpr int enc_stages(int ntp, int elem_bytes, int nw, int wc) {
     const int ks = enc_ks(ntp, elem_bytes);
-    const int stage_b = ks * ntp * 1024 + 64 * (nw / wc) * ks * 16 * elem_bytes;
+    const int stage_b = ks * ntp * 1024 + 32 * enc_tt(ntp, nw, wc) * (nw / wc) * ks * 16 * elem_bytes;
     const int budget = (nw == 4 && wc == 2 && ntp == 6 ? 44 : (nw == 4 && ntp <= 10 ? 72 : 150)) * 1024;
     const int n = budget / stage_b;
     return n < 2 ? 2 : (n > 4 ? 4 : n);
@@ -112,11 +115,11 @@ __host__ __device__ constexpr int enc_aux_bytes(int ntp) { return 512 + ntp * 32
 template <int NTW, int WC, typename XT, int NW>
 __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
                                             const KernelArgs& a, uint4* work) {
-    constexpr int TT = 2;                    // token tiles (of 32) per wave
     constexpr int NTP = NTW * WC;            // coordinate tiles of the padded plan
+    constexpr int TT = enc_tt(NTP, NW, WC);  // token tiles (of 32) per wave
     constexpr int NTH = NW * 64;             // threads of the workgroup
     constexpr int WT = NW / WC;              // waves across tokens
-    constexpr int TOK_WG = 64 * WT;
+    constexpr int TOK_WG = 32 * TT * WT;
     constexpr int KS = enc_ks(NTP, (int)sizeof(XT));
     constexpr int NSTAGE = enc_stages(NTP, (int)sizeof(XT), NW, WC);
     constexpr int SLAB_U4 = KS * NTP * 64;
@@ -194,7 +197,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) xv[ks][tt] = XS::frag(xs, wt * 64 + tt * 32 + l32, ks, h);
+            for (int tt = 0; tt < TT; ++tt) xv[ks][tt] = XS::frag(xs, (wt * TT + tt) * 32 + l32, ks, h);
         uint4 af[3];
         af[0] = abase[0];
         if (NSTEP > 1) af[1] = abase[((1 / NTW) * NTP + (1 % NTW)) * 64];
@@ -261,7 +264,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
     // A: block min/max
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-        const int tw = wt * 64 + tt * 32 + l32;
+        const int tw = (wt * TT + tt) * 32 + l32;
 #pragma unroll
         for (int ct = 0; ct < NTW; ++ct) {
             const f32x16& d = acc[tt][ct];
@@ -307,7 +310,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
             const float qmax = (float)((1u << bits) - 1u);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                const int tw = wt * 64 + tt * 32 + l32;
+                const int tw = (wt * TT + tt) * 32 + l32;
                 const float2 sq = gq[g * TOK_WG + tw];
                 uint32_t* row = rec + tw * rstride;
                 const f32x16& d = acc[tt][ct];
@@ -414,12 +417,14 @@ hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int gri
     return hipLaunchKernel(fn, dim3(grid), dim3(threads), params, lds_bytes, stream);
 }
 
+int encode_tok_wg(int ntw, int wc, int nw) { return 32 * enc_tt(ntw * wc, nw, wc) * (nw / wc); }
+
 // LDS bytes encode_tile needs for a variant (main loop slabs vs epilogue images).
 int encode_lds_bytes(int ntw, int wc, int nw, int n_groups, int rec_dwords, kvtc_dtype dtype) {
     const int ntp = ntw * wc;
     const int eb = dtype == KVTC_BF16 ? 2 : 4;
     const int ks = enc_ks(ntp, eb);
-    const int tok_wg = 64 * (nw / wc);
+    const int tok_wg = 32 * enc_tt(ntp, nw, wc) * (nw / wc);
     const int main_b = enc_stages(ntp, eb, nw, wc) * (ks * ntp * 1024 + tok_wg * ks * (dtype == KVTC_BF16 ? 32 : 64));
     const int epi_b = tok_wg * (2 * ntp * 8 + n_groups * 8 + (rec_dwords + 1) * 4);
     return enc_aux_bytes(ntp) + (main_b > epi_b ? main_b : epi_b);
