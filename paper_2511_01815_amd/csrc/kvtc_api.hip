@@ -188,14 +188,14 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     d.rec_dwords = (int)((total_bits + 31) / 32);
     const int nt = (r + 31) / 32;
 
-    // encode variant: NTW coordinate tiles per wave, WC waves across coordinates, NW waves per workgroup
-    // {waves across coordinates, tiles per wave, one workgroup per compute unit?, waves per workgroup}, ascending padded width
-    // Up to 320 padded coordinates a 4-wave workgroup keeps 64 tokens x all its coordinates in 256
-    // registers per lane and two workgroups share a compute unit (three where 168 registers suffice:
-    // measured 5 % faster on the 6-tile encode).  From 321 to 640, 8-wave workgroups (two waves per
-    // SIMD at 256 registers, 128-token tiles, four waves across the coordinates) measured twice as fast
-    // as 4-wave ones with 512 registers; beyond that only the latter hold a tile.
-    // {waves across coordinates, tiles per wave, workgroups per compute unit, waves per workgroup}
+    // encode variant: NTW coordinate tiles per wave, WC waves across coordinates, NW waves per workgroup.
+    // Up to 320 padded coordinates a 4-wave workgroup keeps its tile (64 tokens per wave across the
+    // tokens; 96 in the 8-tile variant) x all its coordinates in 256 registers per lane and two
+    // workgroups share a compute unit (three where 168 registers suffice: measured 5 % faster on the
+    // 6-tile encode).  From 321 to 640, 8-wave workgroups (two waves per SIMD at 256 registers,
+    // 128-token tiles, four waves across the coordinates) measured twice as fast as 4-wave ones with
+    // 512 registers; beyond that only the latter hold a tile.
+    // {waves across coordinates, tiles per wave, workgroups per compute unit, waves per workgroup}, ascending padded width
     static const int enc_tab[][4] = {{1, 2, 2, 4}, {1, 4, 2, 4}, {2, 3, 3, 4}, {2, 4, 2, 4}, {2, 5, 2, 4},
                                      {4, 3, 1, 8}, {4, 4, 1, 8}, {4, 5, 1, 8}, {4, 6, 1, 4}, {4, 8, 1, 4}};
     d.enc_wc = 0;

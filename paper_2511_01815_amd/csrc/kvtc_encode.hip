@@ -3,22 +3,22 @@
 // (Paper, Section "Method", mode "Compression"; Sections "Feature decorrelation" and
 // "Quantization".)
 //
-// Work decomposition.  A workgroup is 4 wavefronts (one per SIMD, up to 512 registers each)
-// and owns a tile of tokens and ALL kept coordinates of those tokens, because a group's
-// min/max needs every coordinate of the group before any of its codes exists.
+// Work decomposition.  A workgroup (4 wavefronts, or 8 for plans of 321..640 padded coordinates)
+// owns a tile of tokens and ALL kept coordinates of those tokens, because a group's min/max
+// needs every coordinate of the group before any of its codes exists.
 // The product is computed transposed, D^T = V_kept^T X^T, with the 32x32x16 bf16 MFMA:
 // M = coordinates, N = tokens, K = features.  Then a lane owns one token (column) and, by
 // permuting the rows of the A operand, 16 *consecutive* coordinates of it per 32-coordinate
 // tile -- exactly one 16-coordinate block of the record format, so quantisation and packing
 // are lane-local with static bit offsets.
-//   * X is read straight from HBM into the B operand registers (a lane reads 16 contiguous
-//     bytes of its token's row per k-step); every byte of X is read once.
-//   * V_kept is pre-swizzled at plan creation into A-operand fragments; slabs of it are
-//     moved global -> LDS without register staging (double-buffered) and shared by the
-//     wavefronts of the workgroup.
-//   * For wide plans the coordinates are split over WC wavefronts that share the tokens.
+//   * V_kept is pre-swizzled at plan creation into A-operand fragments.  Slabs of it and the
+//     matching columns of the tile's X rows move global -> LDS without register staging, a ring
+//     stage or two ahead of the MFMAs; every byte of X is read from HBM once, the basis slabs
+//     are re-read (from L2) once per tile, so larger token tiles mean less traffic per token.
+//   * The coordinates are split over WC wavefronts that share the tokens; the other wavefronts
+//     take further tokens.  A wavefront holds TT x NTW accumulator tiles of 32 x 32.
 // Epilogue: block min/max -> LDS -> per (token, group) header (fp16 shift down, scale up)
-// -> codes -> OR-ed into the record image in LDS -> one contiguous, coalesced store of the
+// -> codes -> written into the record image in LDS -> one contiguous, coalesced store of the
 // tile's records.
 #include <hip/hip_runtime.h>
 #include "kvtc_dev.h"
