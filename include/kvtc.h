@@ -143,12 +143,15 @@ kvtc_status kvtc_offsets(const kvtc_batch* batch, const kvtc_job* jobs_dev, int 
 /*
  * Encode / decode every job.  x_base_dev is the shared feature array (rows of ld_x
  * elements); job j reads/writes rows x_row0 .. x_row0 + n_tokens - 1 and the stream
- * bytes offsets_dev[j] .. offsets_dev[j+1] - 1 of the shared stream buffer.
+ * bytes offsets_dev[j] .. offsets_dev[j] + n_tokens * R - 1 of the shared stream buffer
+ * (offsets from kvtc_offsets lay the jobs back to back; kvtc_offsets_append gives each job
+ * a place inside a region of its own; offsets_dev[n_jobs] is not read).
  * The host cannot see device-resident sizes without synchronising, so capacity is
- * checked on the device: a job whose stream would end beyond `cap`, or whose plan
+ * checked on the device: a job whose bytes would not lie inside [0, cap), or whose plan
  * index / token count is invalid, is skipped entirely and *status_dev is set to
  * 1 + (index of the lowest such job); it stays 0 when every job ran.  The caller
- * zeroes *status_dev beforehand and reads it after synchronising.
+ * zeroes *status_dev beforehand and reads it after synchronising.  Jobs must not overlap
+ * in the stream buffer (not checked).
  */
 kvtc_status kvtc_encode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs,
                               const void* x_base_dev, kvtc_dtype dtype, int64_t ld_x,
@@ -159,6 +162,52 @@ kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
                               const uint64_t* offsets_dev, void* x_out_base_dev,
                               kvtc_dtype dtype, int64_t ld_x, uint32_t* status_dev,
                               kvtc_stream stream);
+
+/*
+ * ---- Sink tokens, sliding window, incremental coding ------------------------------------
+ * (paper, Section "Sliding Windows and Sink Tokens": the s oldest and the w most recent tokens
+ * are not transform-coded; Section "Experimental setup": the coder runs every c new tokens,
+ * which leaves the window between w - c and w; Appendix "Compression ratio with sliding
+ * window": the sinks are kept in FP8 and the ratio that counts them.)
+ */
+
+/* How a context of ctx tokens divides.  Host only, no GPU call.  A token joins the window when it
+ * arrives; whenever the window holds w tokens its c oldest are coded:
+ *   n_sink = min(ctx, s), n_coded = c * max(0, floor((ctx - s - (w - c)) / c)), n_window = the rest.
+ * KVTC_E_ARG unless ctx >= 0, s >= 0, 1 <= c <= w. */
+typedef struct { int64_t n_sink, n_coded, n_window; } kvtc_split;
+kvtc_status kvtc_window_split(int64_t ctx, int s, int w, int c, kvtc_split* out);
+
+/* ctx / ((ctx - w - s) / cr + w + s / 2): compression ratio of a context of ctx tokens of which w stay
+ * in 16 bits, s in FP8 and the rest is coded at ratio cr.  Host only. */
+double kvtc_cr_with_window(double ctx, double w, double s, double cr);
+
+/*
+ * Sinks to and from FP8 (OCP E4M3, one byte per value, no scale factor: the paper says "FP8" only).
+ * Round to nearest, ties to the even mantissa; magnitudes from 448 up (and infinities) give +-448;
+ * NaN gives 0x7f.  fp32 inputs are first rounded to bf16 like the coder's inputs.
+ *   x_dev     [n_tokens][ld_x] of `dtype`, base and pitch 16-byte aligned, ld_x >= p
+ *   out_dev   [n_tokens][p] bytes; out_cap >= n_tokens * p else KVTC_E_SMALL
+ * Unpacking is exact (every E4M3 value is a bf16 value).  Both are ordered on `stream`, allocate
+ * nothing and do not synchronise; n_tokens == 0 is a no-op.
+ */
+kvtc_status kvtc_fp8_pack(const void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int p, int64_t ld_x,
+                          void* out_dev, size_t out_cap, kvtc_stream stream);
+kvtc_status kvtc_fp8_unpack(const void* in_dev, size_t in_bytes, int64_t n_tokens, int p,
+                            void* x_out_dev, kvtc_dtype dtype, int64_t ld_x, kvtc_stream stream);
+
+/*
+ * Stream offsets for appending to caches that each own a region of the stream buffer, computed on
+ * the GPU:  offsets_dev[j] = region_dev[j] + n_coded_dev[j] * R(plan of job j),  j < n_jobs, and
+ * offsets_dev[n_jobs] = region_dev[n_jobs].  region_dev has n_jobs + 1 ascending entries (byte
+ * offsets of the regions and the end of the last one), n_coded_dev[j] is the number of records
+ * region j already holds and jobs_dev[j].n_tokens the number about to be added.  A job whose region
+ * has no room for them (or whose entry is invalid) gets the offset 2^64 - 1, which
+ * kvtc_encode_batch reports through *status_dev like any job that does not fit.
+ */
+kvtc_status kvtc_offsets_append(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs,
+                                const uint64_t* region_dev, const int64_t* n_coded_dev,
+                                uint64_t* offsets_dev, kvtc_stream stream);
 
 /* Thread-local text for the last non-OK status returned on this thread (static storage). */
 const char* kvtc_last_error(void);

@@ -3,7 +3,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import Optional, Sequence
+from typing import Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -22,6 +22,10 @@ class KvtcError(RuntimeError):
 
 class _Group(C.Structure):
     _fields_ = [("n", C.c_uint16), ("bits", C.c_uint8), ("reserved", C.c_uint8)]
+
+
+class KvtcSplit(C.Structure):
+    _fields_ = [("n_sink", C.c_int64), ("n_coded", C.c_int64), ("n_window", C.c_int64)]
 
 
 def lib_path() -> str:
@@ -62,6 +66,12 @@ def lib() -> C.CDLL:
         L.kvtc_encode_batch.restype = C.c_int
         L.kvtc_decode_batch.argtypes = [vp, vp, C.c_int, vp, sz, vp, vp, C.c_int, i64, vp, vp]
         L.kvtc_decode_batch.restype = C.c_int
+        L.kvtc_window_split.argtypes = [i64, C.c_int, C.c_int, C.c_int, C.POINTER(KvtcSplit)]
+        L.kvtc_cr_with_window.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double]
+        L.kvtc_cr_with_window.restype = C.c_double
+        L.kvtc_fp8_pack.argtypes = [vp, C.c_int, i64, C.c_int, i64, vp, sz, vp]
+        L.kvtc_fp8_unpack.argtypes = [vp, sz, i64, C.c_int, vp, C.c_int, i64, vp]
+        L.kvtc_offsets_append.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp]
         L.kvtc_last_error.argtypes = []
         L.kvtc_last_error.restype = C.c_char_p
         L.kvtc_host_f16_round_down.argtypes = [C.c_float]
@@ -164,6 +174,29 @@ def kvtc_decode_batch(batch: int, jobs_dev, n_jobs: int, in_base_dev, in_bytes: 
                       dtype: int, ld_x: int, status_dev, stream=None) -> None:
     _check(lib().kvtc_decode_batch(batch, _ptr(jobs_dev), n_jobs, _ptr(in_base_dev), in_bytes, _ptr(offsets_dev),
                                    _ptr(x_out_base_dev), dtype, ld_x, _ptr(status_dev), _stream(stream)))
+
+
+def kvtc_window_split(ctx: int, s: int = 4, w: int = 128, c: int = 16) -> Tuple[int, int, int]:
+    out = KvtcSplit()
+    _check(lib().kvtc_window_split(ctx, s, w, c, C.byref(out)))
+    return out.n_sink, out.n_coded, out.n_window
+
+
+def kvtc_cr_with_window(ctx: float, w: float, s: float, cr: float) -> float:
+    return lib().kvtc_cr_with_window(ctx, w, s, cr)
+
+
+def kvtc_fp8_pack(x_dev, dtype: int, n_tokens: int, p: int, ld_x: int, out_dev, out_cap: int, stream=None) -> None:
+    _check(lib().kvtc_fp8_pack(_ptr(x_dev), dtype, n_tokens, p, ld_x, _ptr(out_dev), out_cap, _stream(stream)))
+
+
+def kvtc_fp8_unpack(in_dev, in_bytes: int, n_tokens: int, p: int, x_out_dev, dtype: int, ld_x: int, stream=None) -> None:
+    _check(lib().kvtc_fp8_unpack(_ptr(in_dev), in_bytes, n_tokens, p, _ptr(x_out_dev), dtype, ld_x, _stream(stream)))
+
+
+def kvtc_offsets_append(batch: int, jobs_dev, n_jobs: int, region_dev, n_coded_dev, offsets_dev, stream=None) -> None:
+    _check(lib().kvtc_offsets_append(batch, _ptr(jobs_dev), n_jobs, _ptr(region_dev), _ptr(n_coded_dev), _ptr(offsets_dev),
+                                     _stream(stream)))
 
 
 def make_jobs(plan_idx: Sequence[int], n_tokens: Sequence[int], x_row0: Sequence[int]) -> np.ndarray:

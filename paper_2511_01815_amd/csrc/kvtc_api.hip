@@ -18,6 +18,10 @@ hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int gri
 hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream);
 int encode_lds_bytes(int ntw, int wc, int nw, int n_groups, int rec_dwords, kvtc_dtype dtype);
 int encode_tok_wg(int ntw, int wc, int nw);
+hipError_t launch_fp8_pack(const void* x, kvtc_dtype dtype, int64_t n_tokens, int p, int64_t ld_x, void* out, hipStream_t stream);
+hipError_t launch_fp8_unpack(const void* in, int64_t n_tokens, int p, void* x, kvtc_dtype dtype, int64_t ld_x, hipStream_t stream);
+hipError_t launch_offsets_append(const uint32_t* rec_dwords, int n_plans, const kvtc_job* jobs, int n_jobs, const uint64_t* region,
+                                 const int64_t* n_coded, uint64_t* offsets, hipStream_t stream);
 int decode_rec_bytes(int tt, int rec_dwords);
 int decode_ring_bytes(int nct);
 int decode_stage_u4(int nct);
@@ -500,6 +504,54 @@ kvtc_status kvtc_offsets(const kvtc_batch* batch, const kvtc_job* jobs_dev, int 
                        batch->n_plans, jobs_dev, n_jobs, offsets_dev);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_offsets: launch failed: %s", hipGetErrorString(e));
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_offsets_append(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs, const uint64_t* region_dev,
+                                const int64_t* n_coded_dev, uint64_t* offsets_dev, kvtc_stream stream) {
+    if (!batch || !offsets_dev || !region_dev || n_jobs < 0 || (n_jobs > 0 && (!jobs_dev || !n_coded_dev)))
+        return fail(KVTC_E_ARG, "kvtc_offsets_append: null argument or negative job count");
+    hipError_t e = launch_offsets_append(batch->rec_dwords_dev, batch->n_plans, jobs_dev, n_jobs, region_dev, n_coded_dev, offsets_dev,
+                                         static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_offsets_append: launch failed: %s", hipGetErrorString(e));
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_window_split(int64_t ctx, int s, int w, int c, kvtc_split* out) {
+    if (!out) return fail(KVTC_E_ARG, "kvtc_window_split: null output");
+    if (ctx < 0 || s < 0 || c < 1 || c > w) return fail(KVTC_E_ARG, "kvtc_window_split: need ctx >= 0, s >= 0, 1 <= c <= w (ctx=%lld s=%d w=%d c=%d)", (long long)ctx, s, w, c);
+    out->n_sink = ctx < s ? ctx : s;
+    const int64_t beyond = ctx - s - (int64_t)(w - c);          // window tokens past the w - c that always stay
+    out->n_coded = beyond > 0 ? (beyond / c) * c : 0;
+    out->n_window = ctx - out->n_sink - out->n_coded;
+    return KVTC_OK;
+}
+
+double kvtc_cr_with_window(double ctx, double w, double s, double cr) { return ctx / ((ctx - w - s) / cr + w + s / 2.0); }
+
+kvtc_status kvtc_fp8_pack(const void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int p, int64_t ld_x, void* out_dev, size_t out_cap,
+                          kvtc_stream stream) {
+    if (n_tokens < 0 || n_tokens > 0x7fffffffLL || p <= 0) return fail(KVTC_E_ARG, "kvtc_fp8_pack: n_tokens=%lld p=%d", (long long)n_tokens, p);
+    if (n_tokens == 0) return KVTC_OK;
+    if (!x_dev || !out_dev) return fail(KVTC_E_ARG, "kvtc_fp8_pack: null buffer");
+    kvtc_status st = check_x("kvtc_fp8_pack", x_dev, dtype, ld_x, p);
+    if (st != KVTC_OK) return st;
+    if (out_cap < (size_t)n_tokens * (size_t)p) return fail(KVTC_E_SMALL, "kvtc_fp8_pack: out_cap=%zu < %zu", out_cap, (size_t)n_tokens * (size_t)p);
+    hipError_t e = launch_fp8_pack(x_dev, dtype, n_tokens, p, ld_x, out_dev, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_fp8_pack: launch failed: %s", hipGetErrorString(e));
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_fp8_unpack(const void* in_dev, size_t in_bytes, int64_t n_tokens, int p, void* x_out_dev, kvtc_dtype dtype,
+                            int64_t ld_x, kvtc_stream stream) {
+    if (n_tokens < 0 || n_tokens > 0x7fffffffLL || p <= 0) return fail(KVTC_E_ARG, "kvtc_fp8_unpack: n_tokens=%lld p=%d", (long long)n_tokens, p);
+    if (n_tokens == 0) return KVTC_OK;
+    if (!in_dev || !x_out_dev) return fail(KVTC_E_ARG, "kvtc_fp8_unpack: null buffer");
+    kvtc_status st = check_x("kvtc_fp8_unpack", x_out_dev, dtype, ld_x, p);
+    if (st != KVTC_OK) return st;
+    if (in_bytes < (size_t)n_tokens * (size_t)p) return fail(KVTC_E_SMALL, "kvtc_fp8_unpack: in_bytes=%zu < %zu", in_bytes, (size_t)n_tokens * (size_t)p);
+    hipError_t e = launch_fp8_unpack(in_dev, n_tokens, p, x_out_dev, dtype, ld_x, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_fp8_unpack: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }
 

@@ -76,7 +76,12 @@ __device__ inline uint32_t build_tile_table(const KernelArgs& a, int variant_key
         if (k < per && j < n_jobs) {
             const kvtc_job jb = a.jobs ? a.jobs[j] : a.single;
             bool ok = jb.plan >= 0 && jb.plan < a.n_plans && jb.n_tokens >= 0;
-            if (ok && a.offsets) ok = a.offsets[j + 1] <= a.cap && a.offsets[j + 1] >= a.offsets[j];
+            if (ok && a.offsets) {
+                // the job's own extent must lie inside the buffer (offsets need not be a running sum:
+                // an append writes each job into its own region)
+                const uint64_t off = a.offsets[j], bytes = (uint64_t)jb.n_tokens * (uint64_t)a.plans[jb.plan].rec_dwords * 4ull;
+                ok = off <= a.cap && bytes <= a.cap - off;
+            }
             if (ok) {
                 const PlanDev& pl = a.plans[jb.plan];
                 const int tw = kEncode ? pl.enc_tok_wg : pl.dec_tok_wg;

@@ -103,3 +103,44 @@ def test_job_struct_layout():
     j = kv.make_jobs([0, 1], [5, 7], [0, 5])
     assert j.tobytes() == (b"\x00\x00\x00\x00\x05\x00\x00\x00" + (0).to_bytes(8, "little") +
                            b"\x01\x00\x00\x00\x07\x00\x00\x00" + (5).to_bytes(8, "little"))
+
+
+# ---- sinks / sliding window (host-only entry points) ------------------------------------------
+
+def test_window_split_equals_the_replay():
+    import kvtc_window as kw
+    for s, w, c in [(4, 128, 16), (0, 128, 16), (4, 64, 64), (1, 5, 2), (3, 7, 1), (16, 256, 32)]:
+        for ctx in list(range(0, 3 * w + 2 * s + 9)) + [8192, 131072, 10**9 + 7][: (3 if c > 1 else 0)]:
+            if ctx > 10**6:
+                # the replay is linear in ctx: check the closed form's invariants instead
+                n_sink, n_coded, n_window = kv.kvtc_window_split(ctx, s, w, c)
+                assert n_sink == s and n_coded % c == 0 and w - c <= n_window < w and n_sink + n_coded + n_window == ctx
+            else:
+                assert kv.kvtc_window_split(ctx, s, w, c) == kw.window_split(ctx, s, w, c), (ctx, s, w, c)
+
+
+def test_window_split_and_ratio_reject_and_agree():
+    import kvtc_window as kw
+    for bad in [(-1, 4, 128, 16), (10, -1, 128, 16), (10, 4, 8, 0), (10, 4, 8, 9)]:
+        with pytest.raises(kv.KvtcError) as e:
+            kv.kvtc_window_split(*bad)
+        assert e.value.status == 1
+    st = kv.lib().kvtc_window_split(10, 4, 128, 16, None)
+    assert st == 1 and "null" in kv.kvtc_last_error()
+    for ctx, w, s, cr in [(8192, 128, 4, 20.0), (1000, 112, 4, 16.0), (131072, 127, 0, 40.0), (300, 128, 4, 8.0)]:
+        assert kv.kvtc_cr_with_window(ctx, w, s, cr) == pytest.approx(kw.cr_with_window(ctx, w, s, cr), rel=1e-15)
+
+
+def test_fp8_entry_points_reject_bad_arguments_before_any_launch():
+    L = kv.lib()
+    buf = np.zeros(4096, dtype=np.uint8)
+    ptr = buf.ctypes.data & ~15
+    assert L.kvtc_fp8_pack(None, 0, 0, 1024, 1024, None, 0, None) == 0                 # nothing to do
+    assert L.kvtc_fp8_pack(None, 0, 4, 1024, 1024, ptr, 4096, None) == 1               # null input
+    assert L.kvtc_fp8_pack(ptr, 0, 4, 1024, 512, ptr, 4096, None) == 1                 # pitch below p
+    assert L.kvtc_fp8_pack(ptr, 7, 4, 1024, 1024, ptr, 4096, None) == 1                # unknown dtype
+    assert L.kvtc_fp8_pack(ptr + 2, 0, 4, 1024, 1024, ptr, 4096, None) == 1            # misaligned
+    assert L.kvtc_fp8_pack(ptr, 0, 4, 1024, 1024, ptr, 4095, None) == 3                # output too small
+    assert L.kvtc_fp8_unpack(ptr, 4095, 4, 1024, ptr, 0, 1024, None) == 3
+    assert L.kvtc_fp8_unpack(ptr, 4096, -1, 1024, ptr, 0, 1024, None) == 1
+    assert L.kvtc_offsets_append(None, None, 0, None, None, None, None) == 1
