@@ -65,6 +65,37 @@ def cpu_baseline(bundles, x_host_by_kv, p):
                 host_cpus=len(os.sched_getaffinity(0)))
 
 
+def append_step_latency(kv, batch, x, T, n_jobs, R, stream_buf, dev, c=16, steps=60, warmup=10):
+    """GPU time of kvtc_offsets_append + kvtc_encode_batch for c new tokens in each of n_jobs caches."""
+    import numpy as np
+    import torch
+    if T < 2 * c:
+        return None
+    warmup = min(warmup, T // c - 1)
+    steps = min(steps, T // c - warmup)
+    room = [T * R[j % 2] for j in range(n_jobs)]
+    region = torch.from_numpy(np.concatenate([[0], np.cumsum(room)]).astype(np.int64)).to(dev)
+    cap = int(sum(room))
+    offs = torch.zeros(n_jobs + 1, dtype=torch.int64, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    jobs = [torch.from_numpy(kv.make_jobs([j % 2 for j in range(n_jobs)], [c] * n_jobs,
+                                          [j * T + k * c for j in range(n_jobs)]).view(np.uint8)).to(dev)
+            for k in range(steps + warmup)]
+    coded = [torch.full((n_jobs,), k * c, dtype=torch.int64, device=dev) for k in range(steps + warmup)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * (steps + warmup))]
+    torch.cuda.synchronize()
+    for k in range(steps + warmup):
+        ev[2 * k].record()
+        kv.kvtc_offsets_append(batch.handle, jobs[k], n_jobs, region, coded[k], offs)
+        kv.kvtc_encode_batch(batch.handle, jobs[k], n_jobs, x, kv.KVTC_BF16, 1024, offs, stream_buf, cap, status)
+        ev[2 * k + 1].record()
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0, "an append did not fit its region"
+    us = sorted(ev[2 * k].elapsed_time(ev[2 * k + 1]) * 1e3 for k in range(warmup, warmup + steps))
+    return {"median_us": us[len(us) // 2], "min_us": us[0], "caches": n_jobs, "new_tokens_per_cache": c,
+            "what": "kvtc_offsets_append + kvtc_encode_batch, GPU time between HIP events"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -199,6 +230,10 @@ def main() -> int:
                    "compression": 2.0 * p / R[0], "n_jobs": n_jobs},
         "roofline": roof,
     }
+    # Serving-side latency (not part of `value`): one incremental step of the paper's protocol, the coder
+    # run on the 16 tokens that left each cache's sliding window, all n_jobs caches in one batched launch,
+    # each cache appending to a region of its own in the stream buffer.
+    result["append_step"] = append_step_latency(kv, batch, x, T, n_jobs, R, stream_buf, dev)
     if not args.no_cpu:
         nt = min(args.cpu_tokens, T)
         xs = [ks.bf16_bits_to_f32(x[j * T:j * T + nt].view(torch.int16).cpu().numpy().view(np.uint16)) for j in (0, 1)]
