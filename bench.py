@@ -96,6 +96,20 @@ def append_step_latency(kv, batch, x, T, n_jobs, R, stream_buf, dev, c=16, steps
             "what": "kvtc_offsets_append + kvtc_encode_batch, GPU time between HIP events"}
 
 
+def copy_ceiling(src, dst, reps=5):
+    import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * reps)]
+    dst.copy_(src)
+    for i in range(reps):
+        ev[2 * i].record()
+        dst.copy_(src)
+        ev[2 * i + 1].record()
+    torch.cuda.synchronize()
+    ms = sorted(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(reps))[reps // 2]
+    nbytes = 2 * src.numel() * src.element_size()
+    return {"GBps": nbytes / (ms * 1e-3) / 1e9, "bytes": nbytes, "what": "torch copy of the input tensor, read + write, median of %d" % reps}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -234,6 +248,9 @@ def main() -> int:
     # run on the 16 tokens that left each cache's sliding window, all n_jobs caches in one batched launch,
     # each cache appending to a region of its own in the stream buffer.
     result["append_step"] = append_step_latency(kv, batch, x, T, n_jobs, R, stream_buf, dev)
+    # What a plain device copy of the same input reaches on this machine (reads and writes 2 x raw bytes): the
+    # achievable memory ceiling next to the published 8 TB/s the roofline fraction is quoted against.
+    result["copy_ceiling"] = copy_ceiling(x, x_hat)
     if not args.no_cpu:
         nt = min(args.cpu_tokens, T)
         xs = [ks.bf16_bits_to_f32(x[j * T:j * T + nt].view(torch.int16).cpu().numpy().view(np.uint16)) for j in (0, 1)]
