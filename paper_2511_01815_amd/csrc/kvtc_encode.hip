@@ -353,16 +353,26 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
     }
     __syncthreads();
 
-    // D: the tile's records are contiguous in the stream: one coalesced copy
+    // D: the tile's records are contiguous in the stream: one coalesced copy, 16 bytes per lane when the
+    // tile starts on a 16-byte boundary of the buffer and records are whole 16-byte pieces (then a piece
+    // never straddles two rows of the image), else dword by dword
     {
         const int n_valid = min(TOK_WG, T - tok_tile0);
         uint32_t* out = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.stream_buf) + tr.offset) +
                         (size_t)tok_tile0 * rd;
         const uint32_t magic = 0xffffffffu / (uint32_t)rd + 1u;     // exact floor(i / rd) for i < 2^20
         const int total = n_valid * rd;
-        for (int i = tid; i < total; i += NTH) {
-            const uint32_t t = __umulhi((uint32_t)i, magic);
-            out[i] = rec[t * rstride + ((uint32_t)i - t * rd)];
+        if ((rd & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0u) {
+            for (int i = 4 * tid; i < total; i += 4 * NTH) {
+                const uint32_t t = __umulhi((uint32_t)i, magic);
+                const uint32_t* src = rec + t * rstride + ((uint32_t)i - t * rd);
+                *reinterpret_cast<uint4*>(out + i) = make_uint4(src[0], src[1], src[2], src[3]);
+            }
+        } else {
+            for (int i = tid; i < total; i += NTH) {
+                const uint32_t t = __umulhi((uint32_t)i, magic);
+                out[i] = rec[t * rstride + ((uint32_t)i - t * rd)];
+            }
         }
     }
     __syncthreads();
