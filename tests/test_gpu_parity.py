@@ -365,3 +365,51 @@ def test_batched_ragged_jobs_with_gpu_offsets(c1, c2):
     torch.cuda.synchronize()
     assert offs2.cpu().numpy().tolist() == [0, 10 * oplans[0].record_bytes, 10 * oplans[0].record_bytes]
     assert int(status.item()) == 2
+
+
+def test_batch_with_stream_starts_off_the_16_byte_grid():
+    """A job of a plan with 8-byte records in front shifts the next job's stream start to 8 mod 16 although
+    that job's records are whole 16-byte pieces: encode must fall back to dword stores for it and decode to
+    the skewed record image; both must still give the single-tensor results."""
+    p = 128
+    small = _manual(p, [(16, 1)], 3)                        # 32 header bits + 16 code bits -> 8-byte records
+    wide = _manual(p, [(16, 8), (32, 4), (64, 2)], 4)       # 96 + 128 + 128 + 128 bits -> 60 bytes ...
+    wide16 = _manual(p, [(16, 8), (16, 8), (32, 4), (64, 2)], 5)   # 128 + 128 + 128 + 128 + 128 bits -> 80 bytes = 5 pieces
+    assert small.record_bytes == 8 and wide.record_bytes == 60 and wide16.record_bytes == 80
+    oplans = [small, wide16, wide]
+    gplans = [_gpu_plan(o) for o in oplans]
+    batch = kv.Batch(gplans)
+    lens = [1, 700, 2, 650, 5]
+    pidx = [0, 1, 0, 2, 1]
+    row0 = np.concatenate([[0], np.cumsum(lens)[:-1]])
+    rng = np.random.default_rng(8)
+    scale = np.arange(1, p + 1, dtype=np.float64) ** -0.7
+    Xall = ko.bf16_round(((rng.standard_normal((int(sum(lens)), p)) * scale) @ np.linalg.qr(rng.standard_normal((p, p)))[0]).astype(np.float32))
+    xd = _to_dev(Xall, kv.KVTC_BF16)
+    jobs_dev = torch.from_numpy(kv.make_jobs(pidx, lens, row0).view(np.uint8)).to(DEV)
+    offs = torch.zeros(len(lens) + 1, dtype=torch.int64, device=DEV)
+    kv.kvtc_offsets(batch.handle, jobs_dev, len(lens), offs)
+    torch.cuda.synchronize()
+    want = np.concatenate([[0], np.cumsum([n * oplans[i].record_bytes for n, i in zip(lens, pidx)])])
+    np.testing.assert_array_equal(offs.cpu().numpy(), want)
+    assert want[1] % 16 == 8 and want[3] % 16 != 0            # job 1 (whole pieces) and job 3 start off the grid
+    cap = int(want[-1])
+    out = torch.full((cap + 64,), 0x5A, dtype=torch.uint8, device=DEV)
+    status = torch.zeros(2, dtype=torch.int32, device=DEV)
+    kv.kvtc_encode_batch(batch.handle, jobs_dev, len(lens), xd, kv.KVTC_BF16, p, offs, out, cap, status[0:1])
+    xh = torch.zeros_like(xd)
+    kv.kvtc_decode_batch(batch.handle, jobs_dev, len(lens), out, cap, offs, xh, kv.KVTC_BF16, p, status[1:2])
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    o = out.cpu().numpy()
+    assert np.all(o[cap:] == 0x5A)
+    xh_host = _from_dev(xh)
+    for j, (n, i) in enumerate(zip(lens, pidx)):
+        rec = o[want[j]:want[j + 1]].reshape(n, -1)
+        xv = Xall[row0[j]:row0[j] + n]
+        check_stream(oplans[i], xv, rec, f"job{j}")
+        check_recon(oplans[i], rec, xh_host[row0[j]:row0[j] + n], xv, True, f"job{j}")
+        single = torch.zeros(n * oplans[i].record_bytes, dtype=torch.uint8, device=DEV)
+        kv.kvtc_encode(gplans[i].handle, xd[row0[j]:], kv.KVTC_BF16, n, p, single, single.numel())
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(single.cpu().numpy().reshape(n, -1), rec)
