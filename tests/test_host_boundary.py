@@ -144,3 +144,10 @@ def test_fp8_entry_points_reject_bad_arguments_before_any_launch():
     assert L.kvtc_fp8_unpack(ptr, 4095, 4, 1024, ptr, 0, 1024, None) == 3
     assert L.kvtc_fp8_unpack(ptr, 4096, -1, 1024, ptr, 0, 1024, None) == 1
     assert L.kvtc_offsets_append(None, None, 0, None, None, None, None) == 1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
