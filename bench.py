@@ -9,7 +9,9 @@ replicated as 32 independent seeded draws so that one batch is the 4 GiB of a fu
 8B-shaped 32k-token cache and cannot sit in the 256 MB Infinity Cache.
 Inputs are synthetic, generated on the GPU and resident in HBM before timing starts.
 
-Prints ONE JSON line; see the design doc for the roofline arithmetic.
+Prints ONE JSON line.  Roofline: a launch moves 2p + R algorithmic bytes and does 2 p r bf16
+matrix-core flops per token; the bound is the larger of bytes / 8 TB/s and flops / 2.5 PFLOP/s, and
+the fraction is quoted for the slower of the two kernels from its HIP-event duration.
 """
 from __future__ import annotations
 
@@ -125,8 +127,8 @@ def main() -> int:
                     help="also run one plain device copy of the whole input (known size) for scaling profiler byte counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the path shards with no exchange step; "
-              "see DESIGN.md); use --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (tokens and layers are independent, so the path "
+              "shards with no exchange step); use --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
