@@ -122,7 +122,8 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
 /*
  * Batched / ragged calls: many tensors (jobs), each with its own plan and length, in
  * one launch per direction and per kernel variant among the batch's plans (plans of
- * similar rank share a variant: usually one launch).  A kvtc_batch makes the plans' descriptors addressable
+ * similar rank share a variant: usually one launch; encode adds one small launch per
+ * variant for the jobs of at most 64 tokens, which run on narrower tiles).  A kvtc_batch makes the plans' descriptors addressable
  * from the device; it copies what it needs, but the plans must outlive it.
  * At most 1024 jobs per call (KVTC_E_UNSUPPORTED beyond).
  */

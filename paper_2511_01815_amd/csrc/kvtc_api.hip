@@ -34,6 +34,8 @@ struct kvtc_plan {
     void* blob;             // one device allocation holding everything
     PlanDev* desc_dev;      // the descriptor inside the blob
     size_t record_bytes;
+    int enc_s_wgs;          // short-job encode variant (key in h.enc_s_key, 0 = none): workgroups per compute unit ...
+    int enc_s_lds[2];       // ... and dynamic LDS bytes per element dtype
 };
 
 struct kvtc_batch {
@@ -43,6 +45,7 @@ struct kvtc_batch {
     struct EncVariant { int key, wgs, lds[2]; };        // workgroups per compute unit; lds per element dtype
     struct DecVariant { int key, wgs, rec, ring; };     // workgroups per compute unit; record image, basis ring
     std::vector<EncVariant> enc;
+    std::vector<EncVariant> enc_short;                  // the short-job variants among the plans (64-token tiles)
     std::vector<DecVariant> dec;
     int max_p;
     std::vector<int32_t> rec_dwords;
@@ -228,6 +231,23 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
                     "kvtc_plan_create: record of %d bytes with r=%d needs %d/%d/%d bytes of LDS, %d available",
                     d.rec_dwords * 4, r, d.enc_lds[0], d.enc_lds[1], dec_need, lds_cap);
 
+    // encode variant for short jobs: the same padded width with one wave across the tokens (64-token tiles);
+    // the two widest bulk variants already are of that shape
+    // {padded tiles, waves across coordinates, tiles per wave, waves per workgroup}
+    static const int enc_short_tab[][4] = {{2, 2, 1, 2}, {4, 4, 1, 4}, {6, 2, 3, 2}, {8, 4, 2, 4}, {10, 2, 5, 2},
+                                           {12, 4, 3, 4}, {16, 4, 4, 4}, {20, 4, 5, 4}};
+    d.enc_s_key = 0;
+    int s_wgs = 1, s_lds[2] = {0, 0};
+    for (auto& e : enc_short_tab)
+        if (e[0] == ntp && encode_tok_wg(e[2], e[1], e[3]) == kEncShortTile) {
+            s_lds[KVTC_BF16] = encode_lds_bytes(e[2], e[1], e[3], n_groups, d.rec_dwords, KVTC_BF16);
+            s_lds[KVTC_F32] = encode_lds_bytes(e[2], e[1], e[3], n_groups, d.rec_dwords, KVTC_F32);
+            if (s_lds[0] <= lds_cap && s_lds[1] <= lds_cap) {
+                d.enc_s_key = e[3] * 10000 + e[1] * 100 + e[2];
+                s_wgs = e[3] == 4 && ntp <= 10 ? 2 : 1;          // as the kernel's launch bounds
+            }
+        }
+
     // ---- host images ---------------------------------------------------------------
     const size_t n_venc = (size_t)(p / 16) * ntp * 64 * 8;      // bf16 elements
     const int stage_u4 = decode_stage_u4(d.dec_nct);              // fragments of a 32-feature tile, then its mu entries
@@ -332,6 +352,9 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     pl->blob = blob;
     pl->desc_dev = reinterpret_cast<PlanDev*>(blob + o_desc);
     pl->record_bytes = (size_t)d.rec_dwords * 4;
+    pl->enc_s_wgs = s_wgs;
+    pl->enc_s_lds[0] = s_lds[0];
+    pl->enc_s_lds[1] = s_lds[1];
     *out = pl;
     return KVTC_OK;
 }
@@ -381,10 +404,19 @@ kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dty
     a.stream_buf = out_dev;
     a.cap = out_cap;
     a.status = nullptr;
-    const int64_t tiles = (n_tokens + plan->h.enc_tok_wg - 1) / plan->h.enc_tok_wg;
-    const int slots = cu_count() * plan->h.enc_wgs;
-    const int grid = (int)(tiles < slots ? tiles : slots);
-    hipError_t e = launch_encode(a, dtype, plan->h.enc_nw * 10000 + plan->h.enc_wc * 100 + plan->h.enc_ntw, grid, (size_t)kJobTableBytes + 64 + plan->h.enc_lds[dtype], static_cast<hipStream_t>(stream));
+    // A tensor short enough to give every 64-token tile a compute unit of its own runs the short-job variant.
+    const int64_t tiles_short = (n_tokens + kEncShortTile - 1) / kEncShortTile;
+    hipError_t e;
+    if (plan->h.enc_s_key != 0 && tiles_short <= cu_count()) {
+        a.enc_short = 1;
+        a.enc_short_max = 0x7fffffff;
+        e = launch_encode(a, dtype, plan->h.enc_s_key, (int)tiles_short, (size_t)kJobTableBytes + 64 + plan->enc_s_lds[dtype], static_cast<hipStream_t>(stream));
+    } else {
+        const int64_t tiles = (n_tokens + plan->h.enc_tok_wg - 1) / plan->h.enc_tok_wg;
+        const int slots = cu_count() * plan->h.enc_wgs;
+        const int grid = (int)(tiles < slots ? tiles : slots);
+        e = launch_encode(a, dtype, plan->h.enc_nw * 10000 + plan->h.enc_wc * 100 + plan->h.enc_ntw, grid, (size_t)kJobTableBytes + 64 + plan->h.enc_lds[dtype], static_cast<hipStream_t>(stream));
+    }
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }
@@ -450,6 +482,17 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
             }
             for (int dt = 0; dt < 2; ++dt)
                 if (ph.enc_lds[dt] > v->lds[dt]) v->lds[dt] = ph.enc_lds[dt];
+        }
+        if (ph.enc_s_key != 0) {
+            kvtc_batch::EncVariant* v = nullptr;
+            for (auto& e : b->enc_short)
+                if (e.key == ph.enc_s_key) v = &e;
+            if (!v) {
+                b->enc_short.push_back({ph.enc_s_key, plans[i]->enc_s_wgs, {0, 0}});
+                v = &b->enc_short.back();
+            }
+            for (int dt = 0; dt < 2; ++dt)
+                if (plans[i]->enc_s_lds[dt] > v->lds[dt]) v->lds[dt] = plans[i]->enc_s_lds[dt];
         }
         {
             const int key = ph.dec_tt * 100 + ph.dec_nct;
@@ -592,8 +635,19 @@ kvtc_status kvtc_encode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.cap = out_cap;
     a.status = status_dev;
     if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_encode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
+    // Jobs of at most one 64-token tile go to their plan's short-job variant (one small launch per such
+    // variant: a short job is one workgroup), the rest to the bulk variants.
+    a.enc_short_max = kEncShortTile;
+    a.enc_short = 0;
     for (const auto& v : batch->enc) {
         hipError_t e = launch_encode(a, dtype, v.key, cu_count() * v.wgs,
+                                     (size_t)kJobTableBytes + 64 + v.lds[dtype], static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode_batch: launch failed: %s", hipGetErrorString(e));
+    }
+    a.enc_short = 1;
+    for (const auto& v : batch->enc_short) {
+        const int slots = cu_count() * v.wgs;
+        hipError_t e = launch_encode(a, dtype, v.key, n_jobs < slots ? n_jobs : slots,
                                      (size_t)kJobTableBytes + 64 + v.lds[dtype], static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode_batch: launch failed: %s", hipGetErrorString(e));
     }

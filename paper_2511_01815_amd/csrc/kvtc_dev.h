@@ -12,6 +12,7 @@ constexpr int kThreads = 256;          // 4 wavefronts, one per SIMD of a comput
 constexpr int kMaxJobs = 1024;         // jobs per batched launch (tile table lives in LDS)
 constexpr int kLdsBudget = 160 * 1024; // gfx950 LDS per workgroup
 constexpr int kJobTableBytes = (kMaxJobs + 1) * 4;
+constexpr int kEncShortTile = 64;      // tokens per workgroup tile of the encode variants for short jobs
 
 // Everything a kernel needs to know about a plan.  Lives in device memory and is read
 // through wave-uniform (scalar) loads.
@@ -25,7 +26,7 @@ struct PlanDev {
     int32_t dec_rec_lds, dec_ring_lds;      // decode: bytes of the record image, of the basis ring + mu
     int32_t code_bits_max;                  // widest code of the plan
     int32_t enc_wgs, dec_wgs;               // workgroups per compute unit the variant is built for (1..3)
-    int32_t enc_nw, pad_;                   // encode: waves per workgroup (4 or 8)
+    int32_t enc_nw, enc_s_key;              // encode: waves per workgroup (4 or 8); key of the variant for short jobs (64-token tiles), 0 = none
     const uint4* v_enc;    // [p/16][32*ntp/32][64] MFMA A fragments of V_kept^T (encode)
     const uint4* v_dec;    // [p/32][2*nct*64 + 16] MFMA B fragments of V_kept^T (decode), then the tile's 32 mu entries; tiles 2k, 2k+1 = even, odd features of span k
     const float* negc;     // [32*ntp]  -(mu^T V_kept), zero in the padding
@@ -47,6 +48,8 @@ struct KernelArgs {
     uint64_t cap;              // bytes available in stream_buf
     uint32_t* status;          // device, may be nullptr
     uint32_t dec_ring_off;     // decode: byte offset of the basis ring in the work area; 0 = it shares the record image's space
+    int32_t enc_short;         // encode: this launch runs the short-job variants (jobs of at most enc_short_max tokens whose plan has one) ...
+    int32_t enc_short_max;     // ... and the launches of the bulk variants leave those jobs alone; 0 = no job counts as short
 };
 
 struct TileRef {
@@ -84,10 +87,14 @@ __device__ inline uint32_t build_tile_table(const KernelArgs& a, int variant_key
             }
             if (ok) {
                 const PlanDev& pl = a.plans[jb.plan];
-                const int tw = kEncode ? pl.enc_tok_wg : pl.dec_tok_wg;
-                // each launch serves the plans of its own kernel variant; other launches take the rest
-                if ((kEncode ? pl.enc_nw * 10000 + pl.enc_wc * 100 + pl.enc_ntw : pl.dec_tt * 100 + pl.dec_nct) == variant_key)
-                    tiles = (uint32_t)((jb.n_tokens + tw - 1) / tw);
+                // each launch serves the plans of its own kernel variant; other launches take the rest.
+                // Encode: short jobs go to the plan's short-job variant (narrow tiles), if it has one.
+                const bool is_short = kEncode && pl.enc_s_key != 0 && jb.n_tokens <= a.enc_short_max;
+                int tw = kEncode ? pl.enc_tok_wg : pl.dec_tok_wg;
+                int key = kEncode ? pl.enc_nw * 10000 + pl.enc_wc * 100 + pl.enc_ntw : pl.dec_tt * 100 + pl.dec_nct;
+                if (kEncode && a.enc_short) { tw = kEncShortTile; key = is_short ? pl.enc_s_key : -1; }
+                else if (is_short) key = -1;
+                if (key == variant_key) tiles = (uint32_t)((jb.n_tokens + tw - 1) / tw);
             } else if (first_bad == 0xffffffffu) {
                 first_bad = (uint32_t)j;
             }

@@ -155,6 +155,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
     constexpr int NDMA_MIN = NV_TOTAL / NW + NX_TOTAL / NW;     // transfers per wave per stage, lower bound over waves
     static_assert(TOK_WG % XS::ROWS_PER_DMA == 0, "whole transfers");
     static_assert(3 * (NV + NXD) < 64, "vmcnt range");
+    static_assert(NW >= 2, "waves 0 and 1 fetch the plan's tables");
     char* ring = reinterpret_cast<char*>(smem);
     const uint4* vg = P.v_enc;
     const int n_slabs = p / (16 * KS);
@@ -401,9 +402,14 @@ __global__ void __launch_bounds__(NW * 64, (enc_wgs_per_cu<WC, NTW, NW>())) kvtc
     }
 }
 
-// (waves across coordinates, coordinate tiles per wave, waves per workgroup)
+// (waves across coordinates, coordinate tiles per wave, waves per workgroup): the bulk variants, then
+// the variants for short jobs -- one wave across the tokens, so a 64-token tile and a third of the
+// MFMAs per ring step of the widest bulk tile; a workgroup that has a compute unit to itself (a
+// launch of a few short jobs) is bound by exactly those.  The two widest plans' bulk variants
+// already have 64-token tiles.
 #define KVTC_ENC_VARIANTS(X)                                                                           \
-    X(1, 2, 4) X(1, 4, 4) X(2, 3, 4) X(2, 4, 4) X(2, 5, 4) X(4, 3, 8) X(4, 4, 8) X(4, 5, 8) X(4, 6, 4) X(4, 8, 4)
+    X(1, 2, 4) X(1, 4, 4) X(2, 3, 4) X(2, 4, 4) X(2, 5, 4) X(4, 3, 8) X(4, 4, 8) X(4, 5, 8) X(4, 6, 4) X(4, 8, 4) \
+    X(2, 1, 2) X(4, 1, 4) X(2, 3, 2) X(4, 2, 4) X(2, 5, 2) X(4, 3, 4) X(4, 4, 4) X(4, 5, 4)
 
 // key = 10000 * NW + 100 * WC + NTW
 hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream) {
