@@ -404,10 +404,10 @@ kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dty
     a.stream_buf = out_dev;
     a.cap = out_cap;
     a.status = nullptr;
-    // A tensor short enough to give every 64-token tile a compute unit of its own runs the short-job variant.
+    // A tensor short enough for all its 64-token tiles to run at once (one wave of workgroups) runs the short-job variant.
     const int64_t tiles_short = (n_tokens + kEncShortTile - 1) / kEncShortTile;
     hipError_t e;
-    if (plan->h.enc_s_key != 0 && tiles_short <= cu_count()) {
+    if (plan->h.enc_s_key != 0 && tiles_short <= (int64_t)cu_count() * plan->enc_s_wgs) {
         a.enc_short = 1;
         a.enc_short_max = 0x7fffffff;
         e = launch_encode(a, dtype, plan->h.enc_s_key, (int)tiles_short, (size_t)kJobTableBytes + 64 + plan->enc_s_lds[dtype], static_cast<hipStream_t>(stream));
