@@ -442,12 +442,23 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
     a.ld_x = ld_x;
     a.stream_buf = const_cast<void*>(in_dev);
     a.cap = in_bytes;
-    const int64_t tiles = (n_tokens + plan->h.dec_tok_wg - 1) / plan->h.dec_tok_wg;
     const int slots = cu_count() * plan->h.dec_wgs;
-    const int grid = (int)(tiles < slots ? tiles : slots);
-    const DecLayout lay = decode_layout(plan->h.dec_rec_lds, plan->h.dec_ring_lds, plan->h.dec_wgs);
-    a.dec_ring_off = lay.ring_off;
-    hipError_t e = launch_decode(a, dtype, plan->h.dec_tt * 100 + plan->h.dec_nct, grid, lay.lds_bytes, static_cast<hipStream_t>(stream));
+    // A tensor short enough for all its 128-token tiles to run at once takes the variant with one token
+    // tile per wave (same plan data: it depends on the padded width only).
+    const int64_t tiles_short = (n_tokens + kDecShortTile - 1) / kDecShortTile;
+    hipError_t e;
+    if (plan->h.dec_tt == 2 && tiles_short <= slots) {
+        const DecLayout lay = decode_layout(decode_rec_bytes(1, plan->h.rec_dwords), plan->h.dec_ring_lds, plan->h.dec_wgs);
+        a.dec_ring_off = lay.ring_off;
+        a.dec_short = 1;
+        e = launch_decode(a, dtype, 100 + plan->h.dec_nct, (int)tiles_short, lay.lds_bytes, static_cast<hipStream_t>(stream));
+    } else {
+        const int64_t tiles = (n_tokens + plan->h.dec_tok_wg - 1) / plan->h.dec_tok_wg;
+        const int grid = (int)(tiles < slots ? tiles : slots);
+        const DecLayout lay = decode_layout(plan->h.dec_rec_lds, plan->h.dec_ring_lds, plan->h.dec_wgs);
+        a.dec_ring_off = lay.ring_off;
+        e = launch_decode(a, dtype, plan->h.dec_tt * 100 + plan->h.dec_nct, grid, lay.lds_bytes, static_cast<hipStream_t>(stream));
+    }
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }

@@ -299,6 +299,7 @@ __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, NCT>())) kvtc_de
     uint4* ring = work + a.dec_ring_off / 16u;
     TileRef tr = find_tile(a, tile_start, tile);
     PlanDec P = load_plan_dec(a.plans + tr.plan);
+    P.dec_tok_wg = 4 * 32 * TT;              // this variant's tile (the descriptor holds the bulk variant's)
     issue_records(a, tr, P, lds_offset(work));
     wait_vmem<0>();
     __syncthreads();
@@ -310,6 +311,7 @@ __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, NCT>())) kvtc_de
         if (has_next) {
             trn = find_tile(a, tile_start, next);
             Pn = load_plan_dec(a.plans + trn.plan);
+            Pn.dec_tok_wg = 4 * 32 * TT;
         }
         decode_tile<NCT, TT, OT>(P, tr, a, work, ring, prefetch, has_next && prefetch, trn, Pn);
         if (!has_next) break;
@@ -324,7 +326,12 @@ __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, NCT>())) kvtc_de
     }
 }
 
-#define KVTC_DEC_VARIANTS(X) X(2, 2) X(2, 4) X(2, 6) X(2, 8) X(2, 10) X(2, 12) X(2, 16) X(2, 18) X(2, 20) X(2, 24) X(1, 32)
+// (token tiles per wave, coordinate tiles): the bulk variants, then the same widths with one token tile
+// per wave (128-token workgroup tiles) for single tensors short enough to run all their tiles at once --
+// a workgroup without a neighbour is bound by its own instruction stream, and this halves it
+#define KVTC_DEC_VARIANTS(X)                                                                                   \
+    X(2, 2) X(2, 4) X(2, 6) X(2, 8) X(2, 10) X(2, 12) X(2, 16) X(2, 18) X(2, 20) X(2, 24) X(1, 32)              \
+    X(1, 2) X(1, 4) X(1, 6) X(1, 8) X(1, 10) X(1, 12) X(1, 16) X(1, 18) X(1, 20) X(1, 24)
 
 // key = 100 * TT + NCT
 hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream) {

@@ -13,6 +13,7 @@ constexpr int kMaxJobs = 1024;         // jobs per batched launch (tile table li
 constexpr int kLdsBudget = 160 * 1024; // gfx950 LDS per workgroup
 constexpr int kJobTableBytes = (kMaxJobs + 1) * 4;
 constexpr int kEncShortTile = 64;      // tokens per workgroup tile of the encode variants for short jobs
+constexpr int kDecShortTile = 128;     // the same for decode (one token tile per wave)
 
 // Everything a kernel needs to know about a plan.  Lives in device memory and is read
 // through wave-uniform (scalar) loads.
@@ -50,6 +51,7 @@ struct KernelArgs {
     uint32_t dec_ring_off;     // decode: byte offset of the basis ring in the work area; 0 = it shares the record image's space
     int32_t enc_short;         // encode: this launch runs the short-job variants (jobs of at most enc_short_max tokens whose plan has one) ...
     int32_t enc_short_max;     // ... and the launches of the bulk variants leave those jobs alone; 0 = no job counts as short
+    int32_t dec_short;         // decode: this launch runs the one-token-tile-per-wave variant of every plan (128-token tiles)
 };
 
 struct TileRef {
@@ -92,6 +94,7 @@ __device__ inline uint32_t build_tile_table(const KernelArgs& a, int variant_key
                 const bool is_short = kEncode && pl.enc_s_key != 0 && jb.n_tokens <= a.enc_short_max;
                 int tw = kEncode ? pl.enc_tok_wg : pl.dec_tok_wg;
                 int key = kEncode ? pl.enc_nw * 10000 + pl.enc_wc * 100 + pl.enc_ntw : pl.dec_tt * 100 + pl.dec_nct;
+                if (!kEncode && a.dec_short) { tw = kDecShortTile; key = 100 + pl.dec_nct; }
                 if (kEncode && a.enc_short) { tw = kEncShortTile; key = is_short ? pl.enc_s_key : -1; }
                 else if (is_short) key = -1;
                 if (key == variant_key) tiles = (uint32_t)((jb.n_tokens + tw - 1) / tw);
