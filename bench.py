@@ -123,6 +123,8 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=32768)
     ap.add_argument("--cpu-tokens", type=int, default=32768, help="tokens per tensor in the CPU-baseline sample")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--append", action="store_true",
+                    help="also time one incremental step: 16 new tokens appended to each of the batch's caches")
     ap.add_argument("--copy-check", action="store_true",
                     help="also run one plain device copy of the whole input (known size) for scaling profiler byte counters")
     args = ap.parse_args()
@@ -249,7 +251,9 @@ def main() -> int:
     # Serving-side latency (not part of `value`): one incremental step of the paper's protocol, the coder
     # run on the 16 tokens that left each cache's sliding window, all n_jobs caches in one batched launch,
     # each cache appending to a region of its own in the stream buffer.
-    result["append_step"] = append_step_latency(kv, batch, x, T, n_jobs, R, stream_buf, dev)
+    # (on request only: it launches the encode kernels many more times, which would blur a profile of this run)
+    if args.append:
+        result["append_step"] = append_step_latency(kv, batch, x, T, n_jobs, R, stream_buf, dev)
     # What a plain device copy of the same input reaches on this machine (reads and writes 2 x raw bytes): the
     # achievable memory ceiling next to the published 8 TB/s the roofline fraction is quoted against.
     result["copy_ceiling"] = copy_ceiling(x, x_hat)
