@@ -413,3 +413,49 @@ def test_batch_with_stream_starts_off_the_16_byte_grid():
         kv.kvtc_encode(gplans[i].handle, xd[row0[j]:], kv.KVTC_BF16, n, p, single, single.numel())
         torch.cuda.synchronize()
         np.testing.assert_array_equal(single.cpu().numpy().reshape(n, -1), rec)
+
+
+def test_batch_mixes_short_and_long_jobs_and_plans_without_a_short_variant():
+    """Jobs of at most 64 tokens run on narrow tiles when their plan has such a variant (a separate small
+    launch), others do not; every job must come out as from the single-tensor call."""
+    p = 1024
+    full = _manual(p, [(16, 8), (16, 6), (64, 5), (64, 4), (96, 3), (256, 2), (512, 1)], 11)   # full rank: bulk tiles only
+    mid = _manual(p, [(64, 7), (128, 3)], 12)                                                  # 192 coordinates
+    oplans = [full, mid]
+    gplans = [_gpu_plan(o) for o in oplans]
+    batch = kv.Batch(gplans)
+    lens = [5, 5, 300, 64, 65, 33, 1]
+    pidx = [0, 1, 1, 1, 1, 0, 1]
+    row0 = np.concatenate([[0], np.cumsum(lens)[:-1]])
+    rng = np.random.default_rng(9)
+    scale = np.arange(1, p + 1, dtype=np.float64) ** -0.7
+    Xall = ko.bf16_round(((rng.standard_normal((int(sum(lens)), p)) * scale) @ np.linalg.qr(rng.standard_normal((p, p)))[0]).astype(np.float32))
+    xd = _to_dev(Xall, kv.KVTC_BF16)
+    jobs_dev = torch.from_numpy(kv.make_jobs(pidx, lens, row0).view(np.uint8)).to(DEV)
+    offs = torch.zeros(len(lens) + 1, dtype=torch.int64, device=DEV)
+    kv.kvtc_offsets(batch.handle, jobs_dev, len(lens), offs)
+    torch.cuda.synchronize()
+    want = offs.cpu().numpy()
+    cap = int(want[-1])
+    out = torch.full((cap + 64,), 0x5A, dtype=torch.uint8, device=DEV)
+    status = torch.zeros(2, dtype=torch.int32, device=DEV)
+    kv.kvtc_encode_batch(batch.handle, jobs_dev, len(lens), xd, kv.KVTC_BF16, p, offs, out, cap, status[0:1])
+    xh = torch.zeros_like(xd)
+    kv.kvtc_decode_batch(batch.handle, jobs_dev, len(lens), out, cap, offs, xh, kv.KVTC_BF16, p, status[1:2])
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    o = out.cpu().numpy()
+    assert np.all(o[cap:] == 0x5A)
+    xh_host = _from_dev(xh)
+    for j, (n, i) in enumerate(zip(lens, pidx)):
+        rec = o[want[j]:want[j + 1]].reshape(n, -1)
+        xv = Xall[row0[j]:row0[j] + n]
+        check_stream(oplans[i], xv, rec, f"job{j}")
+        check_recon(oplans[i], rec, xh_host[row0[j]:row0[j] + n], xv, True, f"job{j}")
+        single = torch.zeros(n * oplans[i].record_bytes, dtype=torch.uint8, device=DEV)
+        kv.kvtc_encode(gplans[i].handle, xd[row0[j]:], kv.KVTC_BF16, n, p, single, single.numel())
+        back = torch.zeros((n, p), dtype=torch.bfloat16, device=DEV)
+        kv.kvtc_decode(gplans[i].handle, single, single.numel(), n, back, kv.KVTC_BF16, p)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(single.cpu().numpy().reshape(n, -1), rec)
+        np.testing.assert_array_equal(_from_dev(back), xh_host[row0[j]:row0[j] + n])
