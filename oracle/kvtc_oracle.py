@@ -186,67 +186,62 @@ def dp_allocate(errors: BlockErrors, n_features: int, budget_bits: int,
                 block_sizes: Sequence[int] = (16, 64, 256, 1024),
                 widths: Sequence[int] = (1, 2, 3, 4, 5, 6, 7, 8),
                 header_bits: int = 32, unit: int = 16) -> Tuple[List[Block], float]:
-    """Bit allocation under a per-token budget.
+    """Bit allocation under a per-token budget (paper, appendix "Dynamic programming
+    algorithm": least error over the first i coordinates within b bits, plus the decision
+    that reached it; optimal by induction on i and b).
 
-    The two-table recurrence of the paper's appendix: best_error[i, b] = least
-    squared error using the first i coordinates and at most b bits, everything
-    not yet covered counted as zero-bit; a decision is (type, block size, cost)
-    of the last block.  Types are "None" (zero bits, cost 0: the coordinate is
-    dropped) and uniform min-max quantisation at each width in `widths`, cost
-    n*width + header_bits (the shared 16-bit shift and 16-bit scale).
+    State: gain[i, b] = the least change of the squared error, relative to dropping
+    everything, that the first i coordinates can reach with at most b bits.  The last
+    block of such a prefix has one of the allowed sizes n and a type: "None" (zero bits,
+    cost 0, change 0: the coordinates are dropped) or uniform min-max quantisation at a
+    width w from `widths`, cost n*w + header_bits (the shared 16-bit shift and 16-bit
+    scale), change errors.change(start, n, w).  So
 
-    `unit` is the granularity of block boundaries and of the budget axis.
-    unit=1 is the algorithm exactly as stated (a block may end at any
-    coordinate).  unit=16 adds one restriction: blocks start and end at
-    multiples of 16 coordinates, so every cost is a multiple of 16 bits and the
-    budget axis can be walked in 16-bit steps with the same result.
-    Tie-breaking follows the statement: strict improvement only, block sizes in
-    ascending order, types in listed order.
+        gain[i, b] = min(0, min over (n, type) with cost <= b of gain[i - n, b - cost] + change)
+
+    where the 0 is the prefix left wholly at zero bits (the paper's tables start from that
+    state for every i, which is also what makes a prefix of any length droppable).  A whole
+    row is computed at once: for a fixed last block the candidates over all b are the
+    earlier row shifted right by the block's cost.  "At most b" needs no separate carry
+    from b - 1: the earlier rows are already non-increasing in b.
+
+    `unit` is the granularity of block boundaries and of the budget axis.  unit=1 is the
+    algorithm as stated (a block may end at any coordinate).  unit=16 adds one
+    restriction: blocks start and end at multiples of 16 coordinates, so every cost is a
+    multiple of 16 bits and the budget axis can be walked in 16-bit steps with the same
+    result.  Ties: a candidate replaces the incumbent only when strictly better;
+    candidates are tried with block sizes ascending and types in the listed order.
     Returns (blocks in coordinate order, zero-bit blocks included; best error).
     """
     assert n_features % unit == 0 and header_bits % unit == 0 and all(s % unit == 0 for s in block_sizes)
     nu = n_features // unit
     qb = budget_bits // unit
-    e0 = float(errors.energy[:n_features].sum())
-    best = np.full((nu + 1, qb + 1), e0, dtype=np.float64)
-    dec_w = np.zeros((nu + 1, qb + 1), dtype=np.int32)
-    dec_n = np.zeros((nu + 1, qb + 1), dtype=np.int32)
-    dec_c = np.zeros((nu + 1, qb + 1), dtype=np.int32)
     types = [0] + list(widths)
+    gain = np.zeros((nu + 1, qb + 1), dtype=np.float64)
+    choice = np.full((nu + 1, qb + 1), -1, dtype=np.int32)       # index into `moves` of row i; -1 = prefix dropped
+    moves_of_row: List[List[Tuple[int, int, int]]] = [[]]          # per row: (block units, width, cost units)
     for i in range(1, nu + 1):
-        for size in sorted(block_sizes):
-            su = size // unit
-            if su > i:
+        moves = [(size // unit, w, 0 if w == 0 else (size * w + header_bits) // unit)
+                 for size in sorted(block_sizes) if size // unit <= i for w in types]
+        moves_of_row.append(moves)
+        row = gain[i]
+        for k, (su, w, cost) in enumerate(moves):
+            if cost > qb:
                 continue
-            start = (i - su) * unit
-            cand = []
-            for w in types:
-                cost = 0 if w == 0 else (size * w + header_bits) // unit
-                cand.append((w, cost, errors.change(start, size, w)))
-            for b in range(1, qb + 1):
-                if best[i, b] > best[i, b - 1]:
-                    best[i, b] = best[i, b - 1]
-                    dec_w[i, b] = dec_w[i, b - 1]
-                    dec_n[i, b] = dec_n[i, b - 1]
-                    dec_c[i, b] = dec_c[i, b - 1]
-                for (w, cost, chg) in cand:
-                    if cost <= b:
-                        v = chg + best[i - su, b - cost]
-                        if best[i, b] > v:
-                            best[i, b] = v
-                            dec_w[i, b] = w
-                            dec_n[i, b] = su
-                            dec_c[i, b] = cost
+            cand = gain[i - su, :qb + 1 - cost] + errors.change((i - su) * unit, su * unit, w)
+            better = cand < row[cost:]
+            row[cost:][better] = cand[better]
+            choice[i, cost:][better] = k
     blocks: List[Block] = []
     i, b = nu, qb
-    while i > 0 and dec_n[i, b] > 0:
-        su, w, cost = int(dec_n[i, b]), int(dec_w[i, b]), int(dec_c[i, b])
+    while i > 0 and choice[i, b] >= 0:
+        su, w, cost = moves_of_row[i][int(choice[i, b])]
         blocks.append(Block((i - su) * unit, su * unit, w))
         i, b = i - su, b - cost
-    if i > 0:      # never decided: left at zero bits
+    if i > 0:      # the rest of the prefix was never worth any bits
         blocks.append(Block(0, i * unit, 0))
     blocks.reverse()
-    return blocks, float(best[nu, qb])
+    return blocks, float(errors.energy[:n_features].sum() + gain[nu, qb])
 
 
 def allocation_error(errors: BlockErrors, n_features: int, blocks: Sequence[Block]) -> float:
