@@ -213,16 +213,6 @@ kvtc_status kvtc_offsets_append(const kvtc_batch* batch, const kvtc_job* jobs_de
 /* Thread-local text for the last non-OK status returned on this thread (static storage). */
 const char* kvtc_last_error(void);
 
-/*
- * Host-only helpers that expose the kernels' scalar numerics for CPU tests
- * (no GPU needed): the directed fp32 -> fp16 roundings used for shift (down)
- * and scale (up), and the code decision for one value.
- */
-uint16_t kvtc_host_f16_round_down(float x);
-uint16_t kvtc_host_f16_round_up(float x);
-void kvtc_host_group_header(float lo, float hi, int bits, uint16_t* shift16, uint16_t* scale16);
-uint32_t kvtc_host_code(float d, uint16_t shift16, uint16_t scale16, int bits);
-
 #ifdef __cplusplus
 }
 #endif

@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
         L.kvtc_host_group_header.restype = None
         L.kvtc_host_code.argtypes = [C.c_float, C.c_uint16, C.c_uint16, C.c_int]
         L.kvtc_host_code.restype = C.c_uint32
+        L.kvtc_probe_stream.argtypes = [C.c_int, vp, vp, sz, vp]
+        L.kvtc_probe_mfma_bf16.argtypes = [C.c_int, vp, C.POINTER(C.c_double), vp]
         _lib = L
     return _lib
 
@@ -197,6 +199,20 @@ def kvtc_fp8_unpack(in_dev, in_bytes: int, n_tokens: int, p: int, x_out_dev, dty
 def kvtc_offsets_append(batch: int, jobs_dev, n_jobs: int, region_dev, n_coded_dev, offsets_dev, stream=None) -> None:
     _check(lib().kvtc_offsets_append(batch, _ptr(jobs_dev), n_jobs, _ptr(region_dev), _ptr(n_coded_dev), _ptr(offsets_dev),
                                      _stream(stream)))
+
+
+PROBE_READ, PROBE_WRITE, PROBE_COPY = 0, 1, 2
+
+
+def kvtc_probe_stream(mode: int, src_dev, dst_dev, nbytes: int, stream=None) -> None:
+    _check(lib().kvtc_probe_stream(mode, _ptr(src_dev), _ptr(dst_dev), nbytes, _stream(stream)))
+
+
+def kvtc_probe_mfma_bf16(iters: int, sink_dev, stream=None) -> float:
+    """Launches the matrix-core loop; returns the floating-point operations of the launch."""
+    flops = C.c_double()
+    _check(lib().kvtc_probe_mfma_bf16(iters, _ptr(sink_dev), C.byref(flops), _stream(stream)))
+    return flops.value
 
 
 def make_jobs(plan_idx: Sequence[int], n_tokens: Sequence[int], x_row0: Sequence[int]) -> np.ndarray:

@@ -12,6 +12,7 @@
 
 #include "kvtc_dev.h"
 #include "kvtc_numeric.h"
+#include "../../include/kvtc_test_hooks.h"
 
 namespace kvtc {
 hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream);
@@ -66,16 +67,17 @@ kvtc_status fail(kvtc_status st, const char* fmt, ...) {
 
 float bf16_bits_to_float(uint16_t b) { return bits_f32((uint32_t)b << 16); }
 
+// Compute units of the current device (cached per device).
 int cu_count() {
-    static int n = 0;
-    if (n == 0) {
-        int dev = 0;
+    static int n[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (n[dev] == 0) {
         hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            n = prop.multiProcessorCount;
-        if (n <= 0) n = 256;
+        if (hipGetDeviceProperties(&prop, dev) == hipSuccess) n[dev] = prop.multiProcessorCount;
+        if (n[dev] <= 0) n[dev] = 256;
     }
-    return n;
+    return n[dev];
 }
 
 // Row pitch limit (elements): the kernels address a workgroup tile of up to 256 rows with 32-bit byte offsets.
@@ -150,16 +152,9 @@ void kvtc_host_group_header(float lo, float hi, int bits, uint16_t* shift16, uin
     if (scale16) *scale16 = q.scale16;
 }
 uint32_t kvtc_host_code(float d, uint16_t shift16, uint16_t scale16, int bits) {
-    const float shift = f16_bits_to_f32(shift16);
     const float sc = f16_bits_to_f32(scale16);
-    const float inv = sc > 0.0f ? 1.0f / sc : 0.0f;
-    const float qmax = (float)((1u << bits) - 1u);
-    volatile float t = d - shift;          // two separate fp32 operations, as in the kernel
-    volatile float q = t * inv;
-    float rq = nearbyintf(q);
-    if (!(rq >= 0.0f)) rq = 0.0f;
-    if (rq > qmax) rq = qmax;
-    return (uint32_t)rq;
+    const float inv = sc > 0.0f ? div_rn(1.0f, sc) : 0.0f;          // as group_header derives it
+    return (uint32_t)code_of(d, f16_bits_to_f32(shift16), inv, (float)((1u << bits) - 1u));
 }
 
 kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host, const uint16_t* v_kept_host,

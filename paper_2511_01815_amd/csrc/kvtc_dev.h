@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <mutex>
+#include <utility>
+#include <vector>
 #include "../../include/kvtc.h"
 
 namespace kvtc {
@@ -14,6 +17,22 @@ constexpr int kLdsBudget = 160 * 1024; // gfx950 LDS per workgroup
 constexpr int kJobTableBytes = (kMaxJobs + 1) * 4;
 constexpr int kEncShortTile = 64;      // tokens per workgroup tile of the encode variants for short jobs
 constexpr int kDecShortTile = 128;     // the same for decode (one token tile per wave)
+
+// Lets a kernel use the whole LDS of a compute unit as dynamic shared memory.  The attribute
+// sticks to the (device, function) pair, so it is set on the first launch there only.
+inline hipError_t allow_full_lds(const void* fn) {
+    static std::mutex m;
+    static std::vector<std::pair<int, const void*>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(m);
+    for (const auto& d : done)
+        if (d.first == dev && d.second == fn) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+    if (e == hipSuccess) done.emplace_back(dev, fn);
+    return e;
+}
 
 // Everything a kernel needs to know about a plan.  Lives in device memory and is read
 // through wave-uniform (scalar) loads.

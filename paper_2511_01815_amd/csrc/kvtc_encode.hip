@@ -426,7 +426,7 @@ hipError_t launch_encode(const KernelArgs& a, kvtc_dtype dtype, int key, int gri
 #undef KVTC_X
         default: return hipErrorInvalidValue;
     }
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
+    hipError_t e = allow_full_lds(fn);
     if (e != hipSuccess) return e;
     KernelArgs args = a;
     void* params[] = {&args};

@@ -87,4 +87,21 @@ KVTC_HD GroupQ group_header(float lo, float hi, int bits) {
     return g;
 }
 
+// The code of one coefficient from its group's decoded header: two fp32 operations (subtract the
+// shift, multiply by the rounded reciprocal of the scale), round half to even, clamp to
+// [0, qmax = 2^bits - 1].  inv == 0 (zero scale) gives 0.
+KVTC_HD float code_of(float d, float shift, float inv, float qmax) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const float q = __fmul_rn(__fsub_rn(d, shift), inv);
+    return __builtin_amdgcn_fmed3f(__builtin_rintf(q), 0.0f, qmax);
+#else
+    volatile float t = d - shift;            // kept apart: the host compiler must not fuse them
+    volatile float q = t * inv;
+    float rq = __builtin_nearbyintf(q);
+    if (!(rq >= 0.0f)) rq = 0.0f;
+    if (rq > qmax) rq = qmax;
+    return rq;
+#endif
+}
+
 }  // namespace kvtc

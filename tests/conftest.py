@@ -11,3 +11,29 @@ for pth in (ROOT, os.path.join(ROOT, "oracle")):
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Code / header mismatch rates of every GPU stream that was compared with the oracle, and whether
+    any comparison needed the summation envelope or a second code decision (none may, for calibrated plans)."""
+    mod = sys.modules.get("test_gpu_parity")
+    rates = getattr(mod, "RATES", None) if mod else None
+    if not rates:
+        return
+    tr = terminalreporter
+    tr.write_sep("-", "GPU vs oracle: mismatch rates")
+    worst = {}
+    for st in rates:
+        key = st["label"].split("-job")[0]
+        w = worst.setdefault(key, dict(n=0, code=0.0, hdr=0.0, env=False, red=False, bar=st["code_bar"], hbar=st["hdr_bar"]))
+        w["n"] += 1
+        w["code"] = max(w["code"], st["code_rate"])
+        w["hdr"] = max(w["hdr"], st["hdr_rate"])
+        w["env"] |= st["envelope"]
+        w["red"] |= st["redecided"]
+    for key, w in worst.items():
+        tr.write_line(f"{key:34s} streams {w['n']:3d}  code max {w['code']:.2e} (bar {w['bar']:.1e})  "
+                      f"header max {w['hdr']:.2e} (bar {w['hbar']:.1e})"
+                      f"{'  ENVELOPE' if w['env'] else ''}{'  REDECIDED' if w['red'] else ''}")
+    tr.write_line(f"streams needing the envelope: {sum(s['envelope'] for s in rates)}, "
+                  f"needing a second code decision: {sum(s['redecided'] for s in rates)}")

@@ -85,9 +85,23 @@ def _headers_within_fp32_envelope(oplan, x_vals, d32, sh_g, sc_g, moved, label):
         j += n
 
 
-def check_stream(oplan, x_vals, rec_gpu, label=""):
+RATES = []        # one entry per checked stream; tests/conftest.py prints them in the terminal summary
+
+HDR_BAR = 5e-3    # header mismatches (always exactly one fp16 ulp) on calibrated plans: measured 0 .. 2e-3
+
+
+def check_stream(oplan, x_vals, rec_gpu, label="", hdr_bar=HDR_BAR, weak_coordinates=False):
     """Codes / headers / packing of a GPU stream against the oracle.  x_vals: the bf16-exact
-    input values the kernel saw.  Returns stats."""
+    input values the kernel saw.  Returns stats (also appended to RATES).
+
+    Plans with widths of at most 8 bits (everything calibration produces): the raw code
+    mismatch rate must be <= 1e-4 and the header mismatch rate <= hdr_bar, no second look.
+    `weak_coordinates` marks hand-built plans that keep coordinates far smaller than the terms
+    that cancel in them: their header rate may exceed HDR_BAR up to hdr_bar, provided every
+    differing header lies inside the fp32 summation envelope.  Hand-built plans with widths
+    above 8 bits get the arithmetic bar mean(2^b) * 2^-20, and -- only they -- may have the
+    codes of groups whose header moved re-decided with the GPU's header; that is recorded as
+    `redecided` and shows in the summary."""
     T = x_vals.shape[0]
     assert rec_gpu.shape == (T, oplan.record_bytes)
     d32 = ko.project(oplan, x_vals)
@@ -101,19 +115,25 @@ def check_stream(oplan, x_vals, rec_gpu, label=""):
     hdr_rate = float((sh_ne | sc_ne).mean())
     assert _ulp_apart(sh_g.view(np.uint16), sh_r.view(np.uint16)).max() <= 1, label
     assert _ulp_apart(sc_g.view(np.uint16), sc_r.view(np.uint16)).max() <= 1, label
-    if hdr_rate > 1e-2:
+    envelope = False
+    if hdr_rate > HDR_BAR and int((sh_ne | sc_ne).sum()) > 2:
+        assert weak_coordinates, (label, "header mismatch rate", hdr_rate)
         _headers_within_fp32_envelope(oplan, x_vals, d32, sh_g, sc_g, sh_ne | sc_ne, label)
-        assert hdr_rate <= 1e-1, (label, hdr_rate)
+        envelope = True
+    # (a stream of a few tokens has too few headers for a rate: up to two single-ulp mismatches pass there)
+    assert hdr_rate <= hdr_bar or int((sh_ne | sc_ne).sum()) <= 2, (label, "header mismatch rate", hdr_rate, hdr_bar)
     # codes
     diff = np.abs(co_g.astype(np.int64) - co_r.astype(np.int64))
     rate = float((diff != 0).mean())
     assert diff.max() <= 1, (label, int(diff.max()))
-    # 1e-4 is the bar for the widths calibration produces (<= 8 bits).  A code flips when the
-    # fp32 projection error (relative ~2^-22 of the group range after 64 accumulation steps)
-    # straddles a rounding boundary, i.e. with probability ~2^b * 2^-21 per entry; plans built
-    # by hand with wider codes get that arithmetic bound instead.
-    bar = 1e-4 if oplan.coef_bits.max() <= 8 else max(1e-4, float(np.mean(2.0 ** oplan.coef_bits)) * 2.0 ** -20)
+    # A code flips when the fp32 projection error (relative ~2^-22 of the group range after 64
+    # accumulation steps) straddles a rounding boundary, i.e. with probability ~2^b * 2^-21 per entry:
+    # far inside 1e-4 up to 8 bits; plans built by hand with wider codes get that arithmetic bound.
+    wide = int(oplan.coef_bits.max()) > 8
+    bar = max(1e-4, float(np.mean(2.0 ** oplan.coef_bits)) * 2.0 ** -20) if wide else 1e-4
+    redecided, rate2 = False, None
     if rate > bar:
+        assert wide, (label, "code mismatch rate", rate, bar)
         # a header that moved by one ulp shifts every code boundary of its group; compare
         # those groups against the oracle's decision taken with the GPU's header
         bad_g = (sh_ne | sc_ne)[:, oplan.coef_group]
@@ -125,9 +145,15 @@ def check_stream(oplan, x_vals, rec_gpu, label=""):
         alt = np.clip(np.rint((d32 - sh32) * inv), 0, qmax).astype(np.int64)
         diff2 = np.where(bad_g, np.abs(co_g.astype(np.int64) - alt), diff)
         rate2 = float((diff2 != 0).mean())
+        redecided = True
+        print(f"[parity] {label}: raw code rate {rate:.3e} above {bar:.3e}; codes of moved-header groups re-decided "
+              f"with the GPU's headers: {rate2:.3e}")
         assert diff2.max() <= 1 and rate2 <= bar, (label, rate, rate2)
-        rate = rate2
-    return dict(code_rate=rate, hdr_rate=hdr_rate)
+    st = dict(label=label, code_rate=rate, code_bar=bar, hdr_rate=hdr_rate, hdr_bar=hdr_bar, envelope=envelope,
+              redecided=redecided, code_rate_redecided=rate2, tokens=int(T), r=int(oplan.r),
+              max_bits=int(oplan.coef_bits.max()))
+    RATES.append(st)
+    return st
 
 
 def check_recon(oplan, rec_gpu, xh_gpu, x_vals, out_bf16, label=""):
@@ -141,7 +167,7 @@ def check_recon(oplan, rec_gpu, xh_gpu, x_vals, out_bf16, label=""):
     return err / rng_x
 
 
-def roundtrip(oplan, plan, x_vals, dtype, ld_pad=0, label=""):
+def roundtrip(oplan, plan, x_vals, dtype, ld_pad=0, label="", **bars):
     T, p = x_vals.shape
     ld = p + ld_pad
     xd = torch.zeros((T, ld), dtype=torch.bfloat16 if dtype == kv.KVTC_BF16 else torch.float32, device=DEV)
@@ -160,9 +186,13 @@ def roundtrip(oplan, plan, x_vals, dtype, ld_pad=0, label=""):
         assert torch.all(xh[:, p:] == 7.0), f"{label}: wrote into the row padding"
     xh_host = _from_dev(xh[:, :p].contiguous())
     seen = ko.bf16_round(x_vals)
-    st = check_stream(oplan, seen, rec, label)
+    st = check_stream(oplan, seen, rec, label, **bars)
     st["recon"] = check_recon(oplan, rec, xh_host, seen, dtype == kv.KVTC_BF16, label)
     return st
+
+
+# Hand-built plans over a random orthogonal basis (not a PCA of the data): see check_stream.
+MANUAL_HDR = dict(weak_coordinates=True, hdr_bar=1e-1)
 
 
 # ---- fixtures: calibrated plans ---------------------------------------------------------------------
@@ -262,9 +292,107 @@ def test_manual_plans(name, p, groups):
     scale = np.arange(1, p + 1, dtype=np.float64) ** -0.7
     X = ko.bf16_round(((rng.standard_normal((777, p)) * scale) @ np.linalg.qr(rng.standard_normal((p, p)))[0]
                        + 0.05).astype(np.float32))
-    st = roundtrip(oplan, plan, X, kv.KVTC_BF16, label=name)
-    st2 = roundtrip(oplan, plan, X, kv.KVTC_F32, label=name + "-f32")
+    st = roundtrip(oplan, plan, X, kv.KVTC_BF16, label=name, **MANUAL_HDR)
+    st2 = roundtrip(oplan, plan, X, kv.KVTC_F32, label=name + "-f32", **MANUAL_HDR)
     print(name, st, st2)
+
+
+# One plan per padded width the kernels are built for (32-coordinate tiles: 2, 4, 6, 8, 10, 12, 16, 18, 20, 24, 32),
+# so that every encode and decode variant runs against the oracle in each of its forms.
+VARIANT_RANKS = [64, 128, 192, 256, 320, 384, 512, 576, 640, 768, 1024]
+
+
+def _variant_plan(r):
+    """r kept coordinates of a 1024-feature tensor: 16-coordinate groups of mixed widths in front, then
+    64-coordinate groups, widths falling with the coordinate index."""
+    groups, left = [(16, 8), (16, 7), (16, 5), (16, 6)], r - 64
+    widths = [4, 3, 3, 2, 2, 2, 1, 1]
+    k = 0
+    while left > 0:
+        n = min(64, left) if left % 64 == 0 or left > 64 else left
+        groups.append((n, widths[min(k, len(widths) - 1)]))
+        left -= n
+        k += 1
+    assert sum(n for n, _ in groups) == r
+    return _manual(1024, groups, 100 + r)
+
+
+def _variant_data(T, seed):
+    p = 1024
+    rng = np.random.default_rng(seed)
+    scale = np.arange(1, p + 1, dtype=np.float64) ** -0.7
+    Qx = np.linalg.qr(np.random.default_rng(77).standard_normal((p, p)))[0]
+    return ko.bf16_round(((rng.standard_normal((T, p)) * scale) @ Qx + 0.05).astype(np.float32))
+
+
+@pytest.mark.parametrize("r", VARIANT_RANKS)
+def test_every_kernel_variant_in_every_form(r):
+    """Each padded width has a bulk and a short-job encode kernel and a two-tile and a one-tile decode kernel, each
+    with its own LDS ring, stage and wait-count constants.  Three forms reach them all:
+      (a) a single call of 50 tokens: the short-job encode variant (where the width has one) and the one-tile decode;
+      (b) a single call too long for the short-job path (more 64-token tiles than workgroup slots): bulk encode
+          through the single-tensor arguments, checked on sampled rows and, whole, against form (c);
+      (c) a batch with jobs of 300, 70 and 5 tokens: bulk encode and the short-job launch side by side, bulk decode."""
+    oplan = _variant_plan(r)
+    plan = _gpu_plan(oplan)
+    p, R = 1024, oplan.record_bytes
+    # (a) bf16 and fp32
+    Xa = _variant_data(50, r)
+    roundtrip(oplan, plan, Xa, kv.KVTC_BF16, label=f"variant{r}-short", **MANUAL_HDR)
+    roundtrip(oplan, plan, Xa, kv.KVTC_F32, label=f"variant{r}-short-f32", **MANUAL_HDR)
+    # (c) batch, bf16 and fp32
+    lens = [300, 70, 5]
+    row0 = [0, 300, 370]
+    Xc = _variant_data(375, r + 1)
+    batch = kv.Batch([plan])
+    jobs_dev = torch.from_numpy(kv.make_jobs([0, 0, 0], lens, row0).view(np.uint8)).to(DEV)
+    offs = torch.zeros(4, dtype=torch.int64, device=DEV)
+    kv.kvtc_offsets(batch.handle, jobs_dev, 3, offs)
+    for dtype in (kv.KVTC_BF16, kv.KVTC_F32):
+        xd = _to_dev(Xc, dtype)
+        out = torch.full((375 * R + 64,), 0x5A, dtype=torch.uint8, device=DEV)
+        status = torch.zeros(2, dtype=torch.int32, device=DEV)
+        kv.kvtc_encode_batch(batch.handle, jobs_dev, 3, xd, dtype, p, offs, out, 375 * R, status[0:1])
+        xh = torch.zeros_like(xd)
+        kv.kvtc_decode_batch(batch.handle, jobs_dev, 3, out, 375 * R, offs, xh, dtype, p, status[1:2])
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [0, 0]
+        o = out.cpu().numpy()
+        assert np.all(o[375 * R:] == 0x5A)
+        rec = o[:375 * R].reshape(375, R)
+        tag = f"variant{r}-batch" + ("-f32" if dtype == kv.KVTC_F32 else "")
+        check_stream(oplan, Xc, rec, tag, **MANUAL_HDR)
+        check_recon(oplan, rec, _from_dev(xh), Xc, dtype == kv.KVTC_BF16, tag)
+    # (b) long single call, generated on the GPU; the same rows through a batch of one job must give the same bytes
+    T = 50000
+    g = torch.Generator(device=DEV)
+    g.manual_seed(1000 + r)
+    mix = torch.from_numpy((np.arange(1, p + 1, dtype=np.float64)[:, None] ** -0.7 *
+                            np.linalg.qr(np.random.default_rng(77).standard_normal((p, p)))[0]).astype(np.float32)).to(DEV)
+    xl = (torch.randn((T, p), generator=g, device=DEV) @ mix + 0.05).to(torch.bfloat16)
+    out1 = torch.full((T * R + 64,), 0xA5, dtype=torch.uint8, device=DEV)
+    kv.kvtc_encode(plan.handle, xl, kv.KVTC_BF16, T, p, out1, T * R)
+    xh1 = torch.empty_like(xl)
+    kv.kvtc_decode(plan.handle, out1, T * R, T, xh1, kv.KVTC_BF16, p)
+    jobs1 = torch.from_numpy(kv.make_jobs([0], [T], [0]).view(np.uint8)).to(DEV)
+    offs1 = torch.zeros(2, dtype=torch.int64, device=DEV)
+    kv.kvtc_offsets(batch.handle, jobs1, 1, offs1)
+    out2 = torch.full_like(out1, 0xA5)
+    status = torch.zeros(2, dtype=torch.int32, device=DEV)
+    kv.kvtc_encode_batch(batch.handle, jobs1, 1, xl, kv.KVTC_BF16, p, offs1, out2, T * R, status[0:1])
+    xh2 = torch.empty_like(xl)
+    kv.kvtc_decode_batch(batch.handle, jobs1, 1, out2, T * R, offs1, xh2, kv.KVTC_BF16, p, status[1:2])
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    assert torch.equal(out1, out2), "single call and batch of one job wrote different streams"
+    assert torch.equal(xh1.view(torch.int16), xh2.view(torch.int16)), "single call and batch of one job decoded differently"
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 191, 192, 255, 256, T - 2, T - 1],
+                                     np.random.default_rng(r).integers(0, T, size=200)]))
+    idx = torch.from_numpy(rows).to(DEV)
+    xv = _from_dev(xl.index_select(0, idx))
+    recs = out1[:T * R].view(T, R).index_select(0, idx).cpu().numpy()
+    check_stream(oplan, xv, recs, f"variant{r}-long", **MANUAL_HDR)
+    check_recon(oplan, recs, _from_dev(xh1.index_select(0, idx)), xv, True, f"variant{r}-long")
 
 
 def test_degenerate_inputs(c1):
@@ -338,8 +466,8 @@ def test_batched_ragged_jobs_with_gpu_offsets(c1, c2):
             continue
         rec = o[want[j]:want[j + 1]].reshape(n, -1)
         xv = Xall[row0[j]:row0[j] + n]
-        check_stream(oplans[i], xv, rec, f"job{j}")
-        check_recon(oplans[i], rec, xh_host[row0[j]:row0[j] + n], xv, True, f"job{j}")
+        check_stream(oplans[i], xv, rec, f"ragged-job{j}")
+        check_recon(oplans[i], rec, xh_host[row0[j]:row0[j] + n], xv, True, f"ragged-job{j}")
         # the batched stream equals what the single-tensor entry point writes
         single = torch.zeros(n * oplans[i].record_bytes, dtype=torch.uint8, device=DEV)
         kv.kvtc_encode(gplans[i].handle, xd[row0[j]:], kv.KVTC_BF16, n, 1024, single, single.numel())
@@ -407,8 +535,8 @@ def test_batch_with_stream_starts_off_the_16_byte_grid():
     for j, (n, i) in enumerate(zip(lens, pidx)):
         rec = o[want[j]:want[j + 1]].reshape(n, -1)
         xv = Xall[row0[j]:row0[j] + n]
-        check_stream(oplans[i], xv, rec, f"job{j}")
-        check_recon(oplans[i], rec, xh_host[row0[j]:row0[j] + n], xv, True, f"job{j}")
+        check_stream(oplans[i], xv, rec, f"offgrid-job{j}")
+        check_recon(oplans[i], rec, xh_host[row0[j]:row0[j] + n], xv, True, f"offgrid-job{j}")
         single = torch.zeros(n * oplans[i].record_bytes, dtype=torch.uint8, device=DEV)
         kv.kvtc_encode(gplans[i].handle, xd[row0[j]:], kv.KVTC_BF16, n, p, single, single.numel())
         torch.cuda.synchronize()
@@ -450,8 +578,8 @@ def test_batch_mixes_short_and_long_jobs_and_plans_without_a_short_variant():
     for j, (n, i) in enumerate(zip(lens, pidx)):
         rec = o[want[j]:want[j + 1]].reshape(n, -1)
         xv = Xall[row0[j]:row0[j] + n]
-        check_stream(oplans[i], xv, rec, f"job{j}")
-        check_recon(oplans[i], rec, xh_host[row0[j]:row0[j] + n], xv, True, f"job{j}")
+        check_stream(oplans[i], xv, rec, f"mix-job{j}", **MANUAL_HDR)
+        check_recon(oplans[i], rec, xh_host[row0[j]:row0[j] + n], xv, True, f"mix-job{j}")
         single = torch.zeros(n * oplans[i].record_bytes, dtype=torch.uint8, device=DEV)
         kv.kvtc_encode(gplans[i].handle, xd[row0[j]:], kv.KVTC_BF16, n, p, single, single.numel())
         back = torch.zeros((n, p), dtype=torch.bfloat16, device=DEV)

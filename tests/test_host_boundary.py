@@ -15,7 +15,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "kvtc.h")).read()
+    inc = os.path.join(ROOT, "include")
+    headers = sorted(f for f in os.listdir(inc) if f.endswith(".h"))
+    assert headers == ["kvtc.h", "kvtc_probe.h", "kvtc_test_hooks.h"]
+    hdr = "\n".join(open(os.path.join(inc, f)).read() for f in headers)
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = sorted(set(re.findall(r"\b(kvtc_[a-z0-9_]+)\s*\(", hdr)))
     assert {"kvtc_plan_create", "kvtc_encode", "kvtc_decode", "kvtc_offsets", "kvtc_encode_batch",
