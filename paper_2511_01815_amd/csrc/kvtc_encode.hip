@@ -317,11 +317,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
                 const f32x16& d = acc[tt][ct];
                 uint32_t c[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float q = __fmul_rn(__fsub_rn(d[i], sq.x), sq.y);
-                    q = __builtin_amdgcn_fmed3f(__builtin_rintf(q), 0.0f, qmax);
-                    c[i] = (uint32_t)q;
-                }
+                for (int i = 0; i < 16; ++i) c[i] = (uint32_t)code_of(d[i], sq.x, sq.y, qmax);
                 if (narrow_codes) {
                     char* dst = reinterpret_cast<char*>(row) + (pos0 >> 3);
                     switch (bits) {

@@ -87,21 +87,23 @@ def _headers_within_fp32_envelope(oplan, x_vals, d32, sh_g, sc_g, moved, label):
 
 RATES = []        # one entry per checked stream; tests/conftest.py prints them in the terminal summary
 
-HDR_BAR = 5e-3    # header mismatches (always exactly one fp16 ulp) on calibrated plans: measured 0 .. 2e-3
+# Header mismatches (always exactly one fp16 ulp, always inside the fp32 summation envelope).  Measured over this
+# suite: 0 .. 3.5e-3 of (token, group) pairs on every stream but the 8x plans of the steep-spectrum layers, whose
+# weakest kept groups reach 1.1e-2 (their coordinates are far smaller than the terms that cancel in them); those
+# tests pass a bar of their own.
+HDR_BAR = 1e-2
 
 
-def check_stream(oplan, x_vals, rec_gpu, label="", hdr_bar=HDR_BAR, weak_coordinates=False):
+def check_stream(oplan, x_vals, rec_gpu, label="", hdr_bar=HDR_BAR):
     """Codes / headers / packing of a GPU stream against the oracle.  x_vals: the bf16-exact
     input values the kernel saw.  Returns stats (also appended to RATES).
 
     Plans with widths of at most 8 bits (everything calibration produces): the raw code
-    mismatch rate must be <= 1e-4 and the header mismatch rate <= hdr_bar, no second look.
-    `weak_coordinates` marks hand-built plans that keep coordinates far smaller than the terms
-    that cancel in them: their header rate may exceed HDR_BAR up to hdr_bar, provided every
-    differing header lies inside the fp32 summation envelope.  Hand-built plans with widths
-    above 8 bits get the arithmetic bar mean(2^b) * 2^-20, and -- only they -- may have the
-    codes of groups whose header moved re-decided with the GPU's header; that is recorded as
-    `redecided` and shows in the summary."""
+    mismatch rate must be <= 1e-4, no second look.  Headers: at most one fp16 ulp from the
+    oracle's, every differing one inside the fp32 summation envelope, and their rate <= hdr_bar.
+    Hand-built plans with widths above 8 bits get the arithmetic bar mean(2^b) * 2^-20 for the
+    codes, and -- only they -- may have the codes of groups whose header moved re-decided with
+    the GPU's header; that is printed, recorded as `redecided` and shows in the summary."""
     T = x_vals.shape[0]
     assert rec_gpu.shape == (T, oplan.record_bytes)
     d32 = ko.project(oplan, x_vals)
@@ -115,13 +117,15 @@ def check_stream(oplan, x_vals, rec_gpu, label="", hdr_bar=HDR_BAR, weak_coordin
     hdr_rate = float((sh_ne | sc_ne).mean())
     assert _ulp_apart(sh_g.view(np.uint16), sh_r.view(np.uint16)).max() <= 1, label
     assert _ulp_apart(sc_g.view(np.uint16), sc_r.view(np.uint16)).max() <= 1, label
-    envelope = False
-    if hdr_rate > HDR_BAR and int((sh_ne | sc_ne).sum()) > 2:
-        assert weak_coordinates, (label, "header mismatch rate", hdr_rate)
+    # Any fp32 summation order is a valid projection, so a header may differ from the oracle's (fp64 sum, rounded
+    # once) exactly when the group's extremes moved by no more than the fp32 summation error can move them: every
+    # differing header is held to that envelope, whatever the rate; the rate has a bar of its own on top.
+    n_moved = int((sh_ne | sc_ne).sum())
+    envelope = n_moved > 0
+    if envelope:
         _headers_within_fp32_envelope(oplan, x_vals, d32, sh_g, sc_g, sh_ne | sc_ne, label)
-        envelope = True
     # (a stream of a few tokens has too few headers for a rate: up to two single-ulp mismatches pass there)
-    assert hdr_rate <= hdr_bar or int((sh_ne | sc_ne).sum()) <= 2, (label, "header mismatch rate", hdr_rate, hdr_bar)
+    assert hdr_rate <= hdr_bar or n_moved <= 2, (label, "header mismatch rate", hdr_rate, hdr_bar)
     # codes
     diff = np.abs(co_g.astype(np.int64) - co_r.astype(np.int64))
     rate = float((diff != 0).mean())
@@ -189,10 +193,6 @@ def roundtrip(oplan, plan, x_vals, dtype, ld_pad=0, label="", **bars):
     st = check_stream(oplan, seen, rec, label, **bars)
     st["recon"] = check_recon(oplan, rec, xh_host, seen, dtype == kv.KVTC_BF16, label)
     return st
-
-
-# Hand-built plans over a random orthogonal basis (not a PCA of the data): see check_stream.
-MANUAL_HDR = dict(weak_coordinates=True, hdr_bar=1e-1)
 
 
 # ---- fixtures: calibrated plans ---------------------------------------------------------------------
@@ -292,8 +292,8 @@ def test_manual_plans(name, p, groups):
     scale = np.arange(1, p + 1, dtype=np.float64) ** -0.7
     X = ko.bf16_round(((rng.standard_normal((777, p)) * scale) @ np.linalg.qr(rng.standard_normal((p, p)))[0]
                        + 0.05).astype(np.float32))
-    st = roundtrip(oplan, plan, X, kv.KVTC_BF16, label=name, **MANUAL_HDR)
-    st2 = roundtrip(oplan, plan, X, kv.KVTC_F32, label=name + "-f32", **MANUAL_HDR)
+    st = roundtrip(oplan, plan, X, kv.KVTC_BF16, label=name)
+    st2 = roundtrip(oplan, plan, X, kv.KVTC_F32, label=name + "-f32")
     print(name, st, st2)
 
 
@@ -338,8 +338,8 @@ def test_every_kernel_variant_in_every_form(r):
     p, R = 1024, oplan.record_bytes
     # (a) bf16 and fp32
     Xa = _variant_data(50, r)
-    roundtrip(oplan, plan, Xa, kv.KVTC_BF16, label=f"variant{r}-short", **MANUAL_HDR)
-    roundtrip(oplan, plan, Xa, kv.KVTC_F32, label=f"variant{r}-short-f32", **MANUAL_HDR)
+    roundtrip(oplan, plan, Xa, kv.KVTC_BF16, label=f"variant{r}-short")
+    roundtrip(oplan, plan, Xa, kv.KVTC_F32, label=f"variant{r}-short-f32")
     # (c) batch, bf16 and fp32
     lens = [300, 70, 5]
     row0 = [0, 300, 370]
@@ -361,7 +361,7 @@ def test_every_kernel_variant_in_every_form(r):
         assert np.all(o[375 * R:] == 0x5A)
         rec = o[:375 * R].reshape(375, R)
         tag = f"variant{r}-batch" + ("-f32" if dtype == kv.KVTC_F32 else "")
-        check_stream(oplan, Xc, rec, tag, **MANUAL_HDR)
+        check_stream(oplan, Xc, rec, tag)
         check_recon(oplan, rec, _from_dev(xh), Xc, dtype == kv.KVTC_BF16, tag)
     # (b) long single call, generated on the GPU; the same rows through a batch of one job must give the same bytes
     T = 50000
@@ -391,7 +391,7 @@ def test_every_kernel_variant_in_every_form(r):
     idx = torch.from_numpy(rows).to(DEV)
     xv = _from_dev(xl.index_select(0, idx))
     recs = out1[:T * R].view(T, R).index_select(0, idx).cpu().numpy()
-    check_stream(oplan, xv, recs, f"variant{r}-long", **MANUAL_HDR)
+    check_stream(oplan, xv, recs, f"variant{r}-long")
     check_recon(oplan, recs, _from_dev(xh1.index_select(0, idx)), xv, True, f"variant{r}-long")
 
 
@@ -578,7 +578,7 @@ def test_batch_mixes_short_and_long_jobs_and_plans_without_a_short_variant():
     for j, (n, i) in enumerate(zip(lens, pidx)):
         rec = o[want[j]:want[j + 1]].reshape(n, -1)
         xv = Xall[row0[j]:row0[j] + n]
-        check_stream(oplans[i], xv, rec, f"mix-job{j}", **MANUAL_HDR)
+        check_stream(oplans[i], xv, rec, f"mix-job{j}")
         check_recon(oplans[i], rec, xh_host[row0[j]:row0[j] + n], xv, True, f"mix-job{j}")
         single = torch.zeros(n * oplans[i].record_bytes, dtype=torch.uint8, device=DEV)
         kv.kvtc_encode(gplans[i].handle, xd[row0[j]:], kv.KVTC_BF16, n, p, single, single.numel())

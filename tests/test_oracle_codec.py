@@ -336,8 +336,8 @@ def test_decode_is_a_plain_matrix_product():
 
 def test_committed_bundle_is_what_the_calibration_script_writes():
     """The calibration bundles the benchmark loads are stored values; they must be exactly what the
-    oracle's calibration (PCA + DP allocation at 16x on the seeded config-2 calibration draw) produces,
-    and the hand-set full-rank bundle must keep every coordinate of the same basis."""
+    oracle's calibration (PCA + DP allocation on the seeded config-2 calibration draw) produces -- every
+    ratio of the K tensor -- and the hand-set full-rank bundle must keep every coordinate of the same basis."""
     import os
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     plans_dir = os.path.join(root, "paper_2511_01815_amd", "plans")
@@ -351,7 +351,77 @@ def test_committed_bundle_is_what_the_calibration_script_writes():
     np.testing.assert_array_equal(z["mu32"], plan.mu32)
     assert z["group_n"].tolist() == plan.group_n.tolist() and z["group_bits"].tolist() == plan.group_bits.tolist()
     assert plan.record_bytes * 8 <= info["budget_bits"] == 1024
+    errors = info["errors"]
+    for cr in (8, 20, 40):
+        pl, inf = ko.calibrate_from_pca(C, mu, V, S, float(cr), errors=errors)
+        zz = np.load(os.path.join(plans_dir, f"c2_K_cr{cr}.npz"))
+        np.testing.assert_array_equal(zz["v_bits"], pl.v_bits)
+        np.testing.assert_array_equal(zz["mu32"], pl.mu32)
+        assert zz["group_n"].tolist() == pl.group_n.tolist() and zz["group_bits"].tolist() == pl.group_bits.tolist()
+        assert pl.record_bytes * 8 <= inf["budget_bits"]
     full = np.load(os.path.join(plans_dir, "c2_K_full.npz"))
     assert full["v_bits"].shape == (1024, 1024) and int(full["group_n"].sum()) == 1024
     np.testing.assert_array_equal(full["v_bits"][:, :16], plan.v_bits[:, :16])      # same leading PCA directions
     np.testing.assert_array_equal(full["mu32"], plan.mu32)
+
+
+def _c3_file(layer, kv):
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    return np.load(os.path.join(root, "paper_2511_01815_amd", "plans", f"c3_L{layer:02d}_{kv}.npz"))
+
+
+@pytest.mark.parametrize("layer,kvi", [(3, 0), (20, 1)])
+def test_committed_cache_bundles_are_what_the_calibration_script_writes(layer, kvi):
+    """Two of the 64 per-tensor files of the 32-layer cache, recomputed from scratch (PCA + allocation at 8x, 16x
+    and 20x on the tensor's seeded calibration draw): every stored array must come out again."""
+    wl = ks.WORKLOADS["c3"]
+    L = ks.make_layer(ks.layer_spec("c3", layer, kvi))
+    C = ks.bf16_bits_to_f32(ks.draw_bf16(L, wl.n_calib, ks.CALIB_DRAW))
+    mu, V, S = ko.pca(C)
+    errors = ko.dp_errors(C, mu, V)
+    z = _c3_file(layer, wl.kv[kvi])
+    for cr in (8, 16, 20):
+        plan, info = ko.calibrate_from_pca(C, mu, V, S, float(cr), errors=errors)
+        np.testing.assert_array_equal(z[f"cr{cr}_kept"], plan.kept)
+        np.testing.assert_array_equal(z["v_bits"][:, plan.kept], plan.v_bits)
+        np.testing.assert_array_equal(z["mu32"], plan.mu32)
+        assert z[f"cr{cr}_group_n"].tolist() == plan.group_n.tolist()
+        assert z[f"cr{cr}_group_bits"].tolist() == plan.group_bits.tolist()
+        assert plan.record_bytes * 8 <= info["budget_bits"]
+
+
+def test_every_committed_cache_bundle_is_the_pca_of_its_calibration_draw_within_budget():
+    """All 64 files, without re-running the SVD or the allocation: the stored mean is the mean of the tensor's
+    seeded calibration draw; the stored columns are unit eigenvectors of that draw's covariance with
+    descending eigenvalues (residual of Cov v = lambda v at bf16 storage precision); each ratio's kept
+    groups fill at most the bit budget and more than the budget minus one smallest group; the 16x and 20x
+    kept sets nest inside the 8x one."""
+    wl = ks.WORKLOADS["c3"]
+    for layer in range(wl.n_layers):
+        for kvi, kv_name in enumerate(wl.kv):
+            z = _c3_file(layer, kv_name)
+            spec = ks.layer_spec("c3", layer, kvi)
+            assert int(z["seed"]) == spec.seed and float(z["alpha"]) == spec.alpha
+            L = ks.make_layer(spec)
+            C = ks.bf16_bits_to_f32(ks.draw_bf16(L, wl.n_calib, ks.CALIB_DRAW)).astype(np.float64)
+            mu = C.mean(axis=0)
+            np.testing.assert_array_equal(z["mu32"], mu.astype(np.float32))
+            Vk = ko.bf16_to_f32(z["v_bits"]).astype(np.float64)
+            A = C - mu[None, :]
+            Y = A @ Vk
+            lam = (Y * Y).sum(axis=0) / (np.linalg.norm(Vk, axis=0) ** 2)       # Rayleigh quotients (times n)
+            resid = A.T @ Y - Vk * lam[None, :]
+            assert np.all(np.abs(np.linalg.norm(Vk, axis=0) - 1.0) < 4e-3), (layer, kv_name)
+            assert np.all(np.linalg.norm(resid, axis=0) <= 1.5e-2 * lam[0]), (layer, kv_name, float((np.linalg.norm(resid, axis=0) / lam[0]).max()))
+            # descending: checked on the leading 32 (bf16 storage leaks ~2^-9 of a vector's norm onto the leading
+            # directions, whose eigenvalues are 10^7 times the trailing ones, so small Rayleigh quotients are noisy)
+            assert np.all(np.diff(lam[:32]) <= 1e-2 * lam[:31]) and lam[32:].max() <= lam[31], (layer, kv_name)
+            kept8 = set(z["cr8_kept"].tolist())
+            for cr in (8, 16, 20):
+                n, b, kept = z[f"cr{cr}_group_n"], z[f"cr{cr}_group_bits"], z[f"cr{cr}_kept"]
+                assert int(n.sum()) == kept.size and np.all(n % 16 == 0) and np.all((b >= 1) & (b <= 8))
+                used = 32 * n.size + int((n * b).sum())
+                B = ko.bit_budget(wl.p, cr)
+                assert B - (32 + 16) < used <= B, (layer, kv_name, cr, used, B)
+                assert set(kept.tolist()) <= kept8 or cr == 8
+                assert kept.max() < z["v_bits"].shape[1]
