@@ -165,6 +165,26 @@ kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
                               kvtc_stream stream);
 
 /*
+ * kvtc_encode_batch for callers that cannot allocate device memory or keep a kvtc_batch: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  One call does what
+ * kvtc_batch_create + kvtc_offsets + kvtc_encode_batch do (jobs laid back to back in the stream
+ * buffer) and calls no allocating routine: the plan-descriptor table and the stream offsets live in a
+ * fixed work area inside the library (about 17 KB per GPU, held until the process ends).
+ *   plans             host array of n_plans handles, 1 <= n_plans <= 64 (KVTC_E_UNSUPPORTED beyond);
+ *                     jobs_dev[j].plan indexes it
+ *   offsets_out_dev   NULL, or a device array of n_jobs + 1 entries that receives the offsets
+ *                     (the same values kvtc_offsets gives), e.g. for a later kvtc_decode_batch
+ * Everything else, including *status_dev and the limit of 1024 jobs, is as in kvtc_encode_batch.
+ * All calls on one GPU share the work area: calls on the same stream are ordered; calls that
+ * overlap on one GPU (different streams, or different threads without ordering) race and must
+ * not be made.  Nothing of an earlier call is read by a later one.
+ */
+kvtc_status kvtc_encode_batch_static(const kvtc_plan* const* plans, int n_plans, const kvtc_job* jobs_dev,
+                                     int n_jobs, const void* x_base_dev, kvtc_dtype dtype, int64_t ld_x,
+                                     void* out_base_dev, size_t out_cap, uint64_t* offsets_out_dev,
+                                     uint32_t* status_dev, kvtc_stream stream);
+
+/*
  * ---- Sink tokens, sliding window, incremental coding ------------------------------------
  * (paper, Section "Sliding Windows and Sink Tokens": the s oldest and the w most recent tokens
  * are not transform-coded; Section "Experimental setup": the coder runs every c new tokens,

@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     KVTC_BF16, KVTC_F32, KvtcError, Plan, Batch, lib, lib_path,
     kvtc_plan_create, kvtc_plan_destroy, kvtc_record_bytes, kvtc_encoded_bytes,
     kvtc_encode, kvtc_decode, kvtc_batch_create, kvtc_batch_destroy, kvtc_offsets,
-    kvtc_encode_batch, kvtc_decode_batch, kvtc_last_error, JOB_DTYPE, make_jobs,
+    kvtc_encode_batch, kvtc_decode_batch, kvtc_encode_batch_static, kvtc_last_error, JOB_DTYPE, make_jobs,
     kvtc_window_split, kvtc_cr_with_window, kvtc_fp8_pack, kvtc_fp8_unpack, kvtc_offsets_append,
     kvtc_probe_stream, kvtc_probe_mfma_bf16, PROBE_READ, PROBE_WRITE, PROBE_COPY,
 )

@@ -64,6 +64,8 @@ def lib() -> C.CDLL:
         L.kvtc_offsets.restype = C.c_int
         L.kvtc_encode_batch.argtypes = [vp, vp, C.c_int, vp, C.c_int, i64, vp, vp, sz, vp, vp]
         L.kvtc_encode_batch.restype = C.c_int
+        L.kvtc_encode_batch_static.argtypes = [C.POINTER(vp), C.c_int, vp, C.c_int, vp, C.c_int, i64, vp, sz, vp, vp, vp]
+        L.kvtc_encode_batch_static.restype = C.c_int
         L.kvtc_decode_batch.argtypes = [vp, vp, C.c_int, vp, sz, vp, vp, C.c_int, i64, vp, vp]
         L.kvtc_decode_batch.restype = C.c_int
         L.kvtc_window_split.argtypes = [i64, C.c_int, C.c_int, C.c_int, C.POINTER(KvtcSplit)]
@@ -170,6 +172,13 @@ def kvtc_encode_batch(batch: int, jobs_dev, n_jobs: int, x_base_dev, dtype: int,
                       out_base_dev, out_cap: int, status_dev, stream=None) -> None:
     _check(lib().kvtc_encode_batch(batch, _ptr(jobs_dev), n_jobs, _ptr(x_base_dev), dtype, ld_x, _ptr(offsets_dev),
                                    _ptr(out_base_dev), out_cap, _ptr(status_dev), _stream(stream)))
+
+
+def kvtc_encode_batch_static(plans: Sequence[int], jobs_dev, n_jobs: int, x_base_dev, dtype: int, ld_x: int,
+                             out_base_dev, out_cap: int, offsets_out_dev, status_dev, stream=None) -> None:
+    arr = (C.c_void_p * len(plans))(*plans)
+    _check(lib().kvtc_encode_batch_static(arr, len(plans), _ptr(jobs_dev), n_jobs, _ptr(x_base_dev), dtype, ld_x,
+                                          _ptr(out_base_dev), out_cap, _ptr(offsets_out_dev), _ptr(status_dev), _stream(stream)))
 
 
 def kvtc_decode_batch(batch: int, jobs_dev, n_jobs: int, in_base_dev, in_bytes: int, offsets_dev, x_out_base_dev,

@@ -97,7 +97,7 @@ bool dtype_ok(kvtc_dtype d) { return d == KVTC_BF16 || d == KVTC_F32; }
 size_t elem_size(kvtc_dtype d) { return d == KVTC_BF16 ? 2 : 4; }
 
 __global__ void __launch_bounds__(256) offsets_kernel(const uint32_t* rec_dwords, int n_plans, const kvtc_job* jobs,
-                                                     int n_jobs, uint64_t* offsets) {
+                                                     int n_jobs, uint64_t* offsets, uint64_t* offsets_copy /*may be null*/) {
     __shared__ uint64_t s[256];
     __shared__ uint64_t carry;
     const int tid = threadIdx.x;
@@ -120,12 +120,64 @@ __global__ void __launch_bounds__(256) offsets_kernel(const uint32_t* rec_dwords
             __syncthreads();
         }
         const uint64_t c = carry;
-        if (j < n_jobs) offsets[j] = c + s[tid] - bytes;
+        if (j < n_jobs) {
+            offsets[j] = c + s[tid] - bytes;
+            if (offsets_copy) offsets_copy[j] = c + s[tid] - bytes;
+        }
         __syncthreads();
         if (tid == 255) carry = c + s[255];
         __syncthreads();
     }
-    if (tid == 0) offsets[n_jobs] = carry;
+    if (tid == 0) {
+        offsets[n_jobs] = carry;
+        if (offsets_copy) offsets_copy[n_jobs] = carry;
+    }
+}
+
+// ---- the entry point that allocates nothing ------------------------------------------------------
+// Its plan-descriptor table, record-size table and stream offsets -- what kvtc_batch_create and the
+// caller's offsets buffer hold for kvtc_encode_batch -- live in this file-scope device array.  Every
+// GPU the library runs on holds its own copy (about 17 KB) until the process ends.  The name is a
+// host-side stand-in, not a device address: host code only ever uses the per-device pointer that
+// hipGetSymbolAddress returned for it.
+constexpr int kStaticMaxPlans = 64;
+struct StaticScratch {
+    PlanDev plans[kStaticMaxPlans];
+    uint32_t rec_dwords[kStaticMaxPlans];
+    uint64_t offsets[kMaxJobs + 1];
+};
+static __device__ __align__(256) unsigned char scratch[sizeof(StaticScratch)];
+
+struct PlanPtrs { const PlanDev* p[kStaticMaxPlans]; };
+
+// descriptor of plan i (inside the plan's own device blob) -> table entry i; one thread per dword
+__global__ void __launch_bounds__(256) gather_plans_kernel(const PlanPtrs src, int n_plans, StaticScratch* sc) {
+    constexpr int kDw = (int)(sizeof(PlanDev) / 4);
+    static_assert(sizeof(PlanDev) % 4 == 0, "descriptor is whole dwords");
+    for (int i = threadIdx.x; i < n_plans * kDw; i += blockDim.x) {
+        const int pl = i / kDw, w = i - pl * kDw;
+        reinterpret_cast<uint32_t*>(&sc->plans[pl])[w] = reinterpret_cast<const uint32_t*>(src.p[pl])[w];
+    }
+    for (int i = threadIdx.x; i < n_plans; i += blockDim.x) sc->rec_dwords[i] = (uint32_t)src.p[i]->rec_dwords;
+}
+
+// per-device address of `scratch`, looked up once per device with that device current
+hipError_t static_scratch(StaticScratch** out) {
+    static std::mutex m;
+    static StaticScratch* ptr[64] = {nullptr};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(m);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        ptr[dev] = static_cast<StaticScratch*>(p);
+    }
+    *out = ptr[dev];
+    return hipSuccess;
 }
 
 // Decode LDS layout for one launch: record image and basis ring side by side when both fit (narrow
@@ -550,7 +602,7 @@ kvtc_status kvtc_offsets(const kvtc_batch* batch, const kvtc_job* jobs_dev, int 
     if (!batch || !offsets_dev || n_jobs < 0 || (n_jobs > 0 && !jobs_dev))
         return fail(KVTC_E_ARG, "kvtc_offsets: null argument or negative job count");
     hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), batch->rec_dwords_dev,
-                       batch->n_plans, jobs_dev, n_jobs, offsets_dev);
+                       batch->n_plans, jobs_dev, n_jobs, offsets_dev, static_cast<uint64_t*>(nullptr));
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_offsets: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
@@ -656,6 +708,80 @@ kvtc_status kvtc_encode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
         hipError_t e = launch_encode(a, dtype, v.key, n_jobs < slots ? n_jobs : slots,
                                      (size_t)kJobTableBytes + 64 + v.lds[dtype], static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_encode_batch: launch failed: %s", hipGetErrorString(e));
+    }
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_encode_batch_static(const kvtc_plan* const* plans, int n_plans, const kvtc_job* jobs_dev, int n_jobs,
+                                     const void* x_base_dev, kvtc_dtype dtype, int64_t ld_x, void* out_base_dev, size_t out_cap,
+                                     uint64_t* offsets_out_dev, uint32_t* status_dev, kvtc_stream stream) {
+    const char* who = "kvtc_encode_batch_static";
+    if (!plans || n_plans < 1) return fail(KVTC_E_ARG, "%s: null argument or no plans", who);
+    if (n_plans > kStaticMaxPlans) return fail(KVTC_E_UNSUPPORTED, "%s: %d plans, at most %d per call", who, n_plans, kStaticMaxPlans);
+    if (n_jobs < 0) return fail(KVTC_E_ARG, "%s: n_jobs=%d", who, n_jobs);
+    if (n_jobs > kMaxJobs) return fail(KVTC_E_UNSUPPORTED, "%s: %d jobs, at most %d per call", who, n_jobs, kMaxJobs);
+    if (n_jobs == 0) return KVTC_OK;
+    if (!jobs_dev || !x_base_dev || !out_base_dev || !status_dev) return fail(KVTC_E_ARG, "%s: null buffer", who);
+    if (!dtype_ok(dtype)) return fail(KVTC_E_ARG, "%s: unknown dtype %d", who, (int)dtype);
+    if ((reinterpret_cast<uintptr_t>(x_base_dev) & 15u) || ((size_t)ld_x * elem_size(dtype)) % 16 != 0 || ld_x <= 0)
+        return fail(KVTC_E_ARG, "%s: feature array base and row pitch must be 16-byte aligned", who);
+    if (ld_x > kMaxPitch) return fail(KVTC_E_ARG, "%s: ld_x=%lld above %d", who, (long long)ld_x, kMaxPitch);
+    if (reinterpret_cast<uintptr_t>(out_base_dev) & 15u) return fail(KVTC_E_ARG, "%s: stream buffer must be 16-byte aligned", who);
+    // the kernel variants among the plans and their LDS needs, on the stack
+    struct Variant { int key, wgs, lds; };
+    Variant bulk[kStaticMaxPlans], shrt[kStaticMaxPlans];
+    int n_bulk = 0, n_shrt = 0;
+    PlanPtrs ptrs;
+    for (int i = 0; i < n_plans; ++i) {
+        if (!plans[i]) return fail(KVTC_E_ARG, "%s: plan %d is null", who, i);
+        const PlanDev& ph = plans[i]->h;
+        if (ld_x < ph.p) return fail(KVTC_E_ARG, "%s: ld_x=%lld < p=%d", who, (long long)ld_x, ph.p);
+        ptrs.p[i] = plans[i]->desc_dev;
+        const int key = ph.enc_nw * 10000 + ph.enc_wc * 100 + ph.enc_ntw;
+        int k = 0;
+        while (k < n_bulk && bulk[k].key != key) ++k;
+        if (k == n_bulk) bulk[n_bulk++] = Variant{key, ph.enc_wgs, 0};
+        if (ph.enc_lds[dtype] > bulk[k].lds) bulk[k].lds = ph.enc_lds[dtype];
+        if (ph.enc_s_key != 0) {
+            k = 0;
+            while (k < n_shrt && shrt[k].key != ph.enc_s_key) ++k;
+            if (k == n_shrt) shrt[n_shrt++] = Variant{ph.enc_s_key, plans[i]->enc_s_wgs, 0};
+            if (plans[i]->enc_s_lds[dtype] > shrt[k].lds) shrt[k].lds = plans[i]->enc_s_lds[dtype];
+        }
+    }
+    for (int i = n_plans; i < kStaticMaxPlans; ++i) ptrs.p[i] = nullptr;
+    StaticScratch* sc = nullptr;
+    hipError_t e = static_scratch(&sc);
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "%s: no address for the static work area: %s", who, hipGetErrorString(e));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // every entry the kernels read is written here first, so nothing of an earlier call is seen
+    hipLaunchKernelGGL(gather_plans_kernel, dim3(1), dim3(256), 0, st, ptrs, n_plans, sc);
+    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(256), 0, st, sc->rec_dwords, n_plans, jobs_dev, n_jobs, sc->offsets, offsets_out_dev);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    KernelArgs a;
+    memset(&a, 0, sizeof(a));
+    a.plans = sc->plans;
+    a.n_plans = n_plans;
+    a.jobs = jobs_dev;
+    a.n_jobs = n_jobs;
+    a.offsets = sc->offsets;
+    a.x = x_base_dev;
+    a.ld_x = ld_x;
+    a.stream_buf = out_base_dev;
+    a.cap = out_cap;
+    a.status = status_dev;
+    a.enc_short_max = kEncShortTile;
+    a.enc_short = 0;
+    for (int k = 0; k < n_bulk; ++k) {
+        e = launch_encode(a, dtype, bulk[k].key, cu_count() * bulk[k].wgs, (size_t)kJobTableBytes + 64 + bulk[k].lds, st);
+        if (e != hipSuccess) return fail(KVTC_E_HIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    }
+    a.enc_short = 1;
+    for (int k = 0; k < n_shrt; ++k) {
+        const int slots = cu_count() * shrt[k].wgs;
+        e = launch_encode(a, dtype, shrt[k].key, n_jobs < slots ? n_jobs : slots, (size_t)kJobTableBytes + 64 + shrt[k].lds, st);
+        if (e != hipSuccess) return fail(KVTC_E_HIP, "%s: launch failed: %s", who, hipGetErrorString(e));
     }
     return KVTC_OK;
 }
