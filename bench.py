@@ -129,17 +129,18 @@ def ceilings(kv, src, dst, reps=7):
         ms = statistics.median(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(reps))
         out[name + "_GBps"] = moved / (ms * 1e-3) / 1e9
     sink = torch.zeros(4, dtype=torch.float32, device=src.device)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * reps)]
-    flops = kv.kvtc_probe_mfma_bf16(4000, sink)
-    for i in range(reps):
-        ev[2 * i].record()
-        flops = kv.kvtc_probe_mfma_bf16(4000, sink)
-        ev[2 * i + 1].record()
-    torch.cuda.synchronize()
-    ms = statistics.median(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(reps))
-    out["mfma_bf16_TFLOPs"] = flops / (ms * 1e-3) / 1e12
+    for key, rnd in (("mfma_bf16_TFLOPs", 0), ("mfma_bf16_random_operands_TFLOPs", 1)):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * reps)]
+        flops = kv.kvtc_probe_mfma_bf16(4000, rnd, sink)
+        for i in range(reps):
+            ev[2 * i].record()
+            flops = kv.kvtc_probe_mfma_bf16(4000, rnd, sink)
+            ev[2 * i + 1].record()
+        torch.cuda.synchronize()
+        ms = statistics.median(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(reps))
+        out[key] = flops / (ms * 1e-3) / 1e12
     out["what"] = (f"kvtc_probe_stream over {nbytes / 2**30:.2f} GiB (read / write / copy = read + write bytes) and "
-                   f"kvtc_probe_mfma_bf16, medians of {reps}")
+                   f"kvtc_probe_mfma_bf16 (operands of eight small values / pseudo-random operands), medians of {reps}")
     return out
 
 

@@ -28,10 +28,13 @@ kvtc_status kvtc_probe_stream(kvtc_probe_mode mode, const void* src_dev, void* d
                               kvtc_stream stream);
 
 /* Every wavefront of a grid that fills the device runs `iters` rounds of eight independent
- * v_mfma_f32_32x32x16_bf16 on register operands.  *flops_host receives the floating-point operations
- * of the launch (2 * 32 * 32 * 16 per instruction).  sink_dev (>= 4 bytes) is written only if a result
- * is NaN, which the operands never produce. */
-kvtc_status kvtc_probe_mfma_bf16(int iters, void* sink_dev, double* flops_host, kvtc_stream stream);
+ * v_mfma_f32_32x32x16_bf16 on register operands.  random_operands = 0: the operands take eight small
+ * values; 1: pseudo-random bf16 values of both signs, different from one instruction to the next, as
+ * the coder's operands are -- the rate the matrix cores sustain depends on it (the chip lowers its
+ * clock under the higher switching activity), so both are reported.  *flops_host receives the
+ * floating-point operations of the launch (2 * 32 * 32 * 16 per instruction).  sink_dev (>= 4 bytes)
+ * is written only if a result is NaN.  KVTC_E_ARG on iters < 1, a flag outside 0..1 or a null pointer. */
+kvtc_status kvtc_probe_mfma_bf16(int iters, int random_operands, void* sink_dev, double* flops_host, kvtc_stream stream);
 
 #ifdef __cplusplus
 }

@@ -85,7 +85,7 @@ def lib() -> C.CDLL:
         L.kvtc_host_code.argtypes = [C.c_float, C.c_uint16, C.c_uint16, C.c_int]
         L.kvtc_host_code.restype = C.c_uint32
         L.kvtc_probe_stream.argtypes = [C.c_int, vp, vp, sz, vp]
-        L.kvtc_probe_mfma_bf16.argtypes = [C.c_int, vp, C.POINTER(C.c_double), vp]
+        L.kvtc_probe_mfma_bf16.argtypes = [C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
         _lib = L
     return _lib
 
@@ -217,10 +217,10 @@ def kvtc_probe_stream(mode: int, src_dev, dst_dev, nbytes: int, stream=None) -> 
     _check(lib().kvtc_probe_stream(mode, _ptr(src_dev), _ptr(dst_dev), nbytes, _stream(stream)))
 
 
-def kvtc_probe_mfma_bf16(iters: int, sink_dev, stream=None) -> float:
+def kvtc_probe_mfma_bf16(iters: int, random_operands: int, sink_dev, stream=None) -> float:
     """Launches the matrix-core loop; returns the floating-point operations of the launch."""
     flops = C.c_double()
-    _check(lib().kvtc_probe_mfma_bf16(iters, _ptr(sink_dev), C.byref(flops), _stream(stream)))
+    _check(lib().kvtc_probe_mfma_bf16(iters, random_operands, _ptr(sink_dev), C.byref(flops), _stream(stream)))
     return flops.value
 
 

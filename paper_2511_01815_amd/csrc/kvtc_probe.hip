@@ -40,13 +40,34 @@ __global__ void __launch_bounds__(kProbeThreads) probe_stream_kernel(const uint4
         reinterpret_cast<uint32_t*>(dst)[0] = acc.w;       // keeps the loads alive; practically never taken
 }
 
+// RANDOM = 0: operands take eight small values (little switching in the multipliers); 1: every operand
+// register holds pseudo-random bf16 values of both signs with exponents spread over 2^-4 .. 2^3, and
+// successive instructions see different operands -- what the coder's products look like to the matrix cores.
+template <int RANDOM>
 __global__ void __launch_bounds__(kProbeThreads) probe_mfma_kernel(int iters, float* sink) {
     const int lane = threadIdx.x & 63;
-    bf16x8p a, b;
+    bf16x8p a[4], b[2];
+    if (RANDOM) {
+        uint32_t st = 0x9e3779b9u * (uint32_t)(blockIdx.x * kProbeThreads + threadIdx.x + 1);
+        auto next_pair = [&]() {                   // two bf16 values: random sign and mantissa, exponent 123..130
+            st = st * 1664525u + 1013904223u;
+            const uint32_t r = st >> 4;
+            const uint32_t lo = ((r & 0x8000u) | ((123u + ((r >> 7) & 7u)) << 7) | (r & 0x7fu)) & 0xffffu;
+            const uint32_t r2 = st >> 14;
+            const uint32_t hi = ((r2 & 0x8000u) | ((123u + ((r2 >> 7) & 7u)) << 7) | (r2 & 0x7fu)) & 0xffffu;
+            return lo | (hi << 16);
+        };
+        for (int k = 0; k < 4; ++k) a[k] = __builtin_bit_cast(bf16x8p, make_uint4(next_pair(), next_pair(), next_pair(), next_pair()));
+        for (int k = 0; k < 2; ++k) b[k] = __builtin_bit_cast(bf16x8p, make_uint4(next_pair(), next_pair(), next_pair(), next_pair()));
+    } else {
+        bf16x8p a0, b0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        a[e] = (__bf16)(0.001f * (float)((lane + e) & 7));
-        b[e] = (__bf16)(0.002f * (float)((lane * 3 + e) & 7));
+        for (int e = 0; e < 8; ++e) {
+            a0[e] = (__bf16)(0.001f * (float)((lane + e) & 7));
+            b0[e] = (__bf16)(0.002f * (float)((lane * 3 + e) & 7));
+        }
+        for (int k = 0; k < 4; ++k) a[k] = a0;
+        for (int k = 0; k < 2; ++k) b[k] = b0;
     }
     f32x16p acc[8];
 #pragma unroll
@@ -55,7 +76,7 @@ __global__ void __launch_bounds__(kProbeThreads) probe_mfma_kernel(int iters, fl
         for (int e = 0; e < 16; ++e) acc[k][e] = 0.0f;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[k], 0, 0, 0);
+        for (int k = 0; k < 8; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[k & 3], b[k >> 2], acc[k], 0, 0, 0);
     }
     float s = 0.0f;
 #pragma unroll
@@ -92,15 +113,19 @@ kvtc_status kvtc_probe_stream(kvtc_probe_mode mode, const void* src_dev, void* d
     return hipGetLastError() == hipSuccess ? KVTC_OK : KVTC_E_HIP;
 }
 
-kvtc_status kvtc_probe_mfma_bf16(int iters, void* sink_dev, double* flops_host, kvtc_stream stream) {
-    if (iters < 1 || !sink_dev || !flops_host) return KVTC_E_ARG;
+kvtc_status kvtc_probe_mfma_bf16(int iters, int random_operands, void* sink_dev, double* flops_host, kvtc_stream stream) {
+    if (iters < 1 || !sink_dev || !flops_host || random_operands < 0 || random_operands > 1) return KVTC_E_ARG;
     int dev = 0, cus = 256;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
         cus = prop.multiProcessorCount;
     const int grid = cus * 2;                      // two 4-wave workgroups per compute unit: two waves per SIMD
-    hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), iters,
-                       static_cast<float*>(sink_dev));
+    if (random_operands)
+        hipLaunchKernelGGL(probe_mfma_kernel<1>, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), iters,
+                           static_cast<float*>(sink_dev));
+    else
+        hipLaunchKernelGGL(probe_mfma_kernel<0>, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), iters,
+                           static_cast<float*>(sink_dev));
     if (hipGetLastError() != hipSuccess) return KVTC_E_HIP;
     *flops_host = (double)grid * (kProbeThreads / 64) * (double)iters * 8.0 * 2.0 * 32.0 * 32.0 * 16.0;
     return KVTC_OK;
