@@ -44,7 +44,7 @@ struct kvtc_batch {
     int n_plans;
     // the kernel variants the plans use (a launch per variant), with the LDS maxima over each one's plans
     struct EncVariant { int key, wgs, lds[2]; };        // workgroups per compute unit; lds per element dtype
-    struct DecVariant { int key, wgs, rec, ring; };     // workgroups per compute unit; record image, basis ring
+    struct DecVariant { int key, wgs, rec, ring; };     // workgroups per compute unit; record image, basis ring (the widest among the class's plans)
     std::vector<EncVariant> enc;
     std::vector<EncVariant> enc_short;                  // the short-job variants among the plans (64-token tiles)
     std::vector<DecVariant> dec;
@@ -255,12 +255,15 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
     d.enc_wc = 0;
     for (auto& e : enc_tab)
         if (e[0] * e[1] >= nt) { d.enc_wc = e[0]; d.enc_ntw = e[1]; d.enc_wgs = e[2]; d.enc_nw = e[3]; break; }
-    // {token tiles per wave, coordinate tiles, workgroups per compute unit}
-    static const int dec_tab[][3] = {{2, 2, 3}, {2, 4, 3}, {2, 6, 2}, {2, 8, 2}, {2, 10, 2},
-                                     {2, 12, 1}, {2, 16, 1}, {2, 18, 1}, {2, 20, 1}, {2, 24, 1}, {1, 32, 1}};
+    // decode: the widths the kernels are built for, with the register class (= its widest member) that serves each;
+    // odd widths where the calibrated plans of the 8B-shaped cache fall (224 = 7, 272 = 9, 528 = 17 tiles): in decode
+    // the coordinates are the contraction index, so a tile less is that much less matrix work and basis traffic
+    // {token tiles per wave, coordinate tiles, class, workgroups per compute unit}
+    static const int dec_tab[][4] = {{2, 2, 4, 3}, {2, 4, 4, 3}, {2, 6, 10, 2}, {2, 7, 10, 2}, {2, 8, 10, 2}, {2, 9, 10, 2}, {2, 10, 10, 2},
+                                     {2, 12, 18, 1}, {2, 16, 18, 1}, {2, 17, 18, 1}, {2, 18, 18, 1}, {2, 20, 24, 1}, {2, 24, 24, 1}, {1, 32, 32, 1}};
     d.dec_tt = 0;
     for (auto& e : dec_tab)
-        if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; d.dec_wgs = e[2]; break; }
+        if (e[1] >= nt) { d.dec_tt = e[0]; d.dec_nct = e[1]; d.dec_cls = e[2]; d.dec_wgs = e[3]; break; }
     if (d.enc_wc == 0 || d.dec_tt == 0) return fail(KVTC_E_UNSUPPORTED, "kvtc_plan_create: no kernel variant for r=%d", r);
     const int ntp = d.enc_ntw * d.enc_wc;
     d.enc_tok_wg = encode_tok_wg(d.enc_ntw, d.enc_wc, d.enc_nw);
@@ -498,13 +501,13 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
         const DecLayout lay = decode_layout(decode_rec_bytes(1, plan->h.rec_dwords), plan->h.dec_ring_lds, plan->h.dec_wgs);
         a.dec_ring_off = lay.ring_off;
         a.dec_short = 1;
-        e = launch_decode(a, dtype, 100 + plan->h.dec_nct, (int)tiles_short, lay.lds_bytes, static_cast<hipStream_t>(stream));
+        e = launch_decode(a, dtype, 100 + plan->h.dec_cls, (int)tiles_short, lay.lds_bytes, static_cast<hipStream_t>(stream));
     } else {
         const int64_t tiles = (n_tokens + plan->h.dec_tok_wg - 1) / plan->h.dec_tok_wg;
         const int grid = (int)(tiles < slots ? tiles : slots);
         const DecLayout lay = decode_layout(plan->h.dec_rec_lds, plan->h.dec_ring_lds, plan->h.dec_wgs);
         a.dec_ring_off = lay.ring_off;
-        e = launch_decode(a, dtype, plan->h.dec_tt * 100 + plan->h.dec_nct, grid, lay.lds_bytes, static_cast<hipStream_t>(stream));
+        e = launch_decode(a, dtype, plan->h.dec_tt * 100 + plan->h.dec_cls, grid, lay.lds_bytes, static_cast<hipStream_t>(stream));
     }
     if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
@@ -553,7 +556,7 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
                 if (plans[i]->enc_s_lds[dt] > v->lds[dt]) v->lds[dt] = plans[i]->enc_s_lds[dt];
         }
         {
-            const int key = ph.dec_tt * 100 + ph.dec_nct;
+            const int key = ph.dec_tt * 100 + ph.dec_cls;
             kvtc_batch::DecVariant* v = nullptr;
             for (auto& e : b->dec)
                 if (e.key == key) v = &e;

@@ -124,8 +124,8 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
     constexpr int TOK_WG = 4 * TOK_W;
     constexpr int SLAB_U4 = 2 * NCT * 64;          // one 32-feature tile of V_kept
     constexpr int STAGE_U4 = SLAB_U4 + kMuU4;
-    constexpr int NV = SLAB_U4 / kThreads;
-    static_assert(SLAB_U4 % kThreads == 0, "whole transfers");
+    constexpr int NV = (SLAB_U4 + kThreads - 1) / kThreads;     // transfer rounds of the workgroup per slab; with an odd tile count the last one is half a round (waves 0 and 1)
+    static_assert(SLAB_U4 % 128 == 0, "whole wave transfers");
     static_assert(kDecStages == 2, "the wait counts below are written out for a ring of two slabs");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -146,7 +146,8 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
         const uint32_t dst = lds_ring + (uint32_t)(stage * STAGE_U4) * 16u;
 #pragma unroll
         for (int i = 0; i < NV; ++i)
-            dma16_async(vsrc + i * kThreads, (uint32_t)tid * 16u, dst + (uint32_t)(i * kThreads + wave * 64) * 16u);
+            if (i * kThreads + wave * 64 < SLAB_U4)
+                dma16_async(vsrc + i * kThreads, (uint32_t)tid * 16u, dst + (uint32_t)(i * kThreads + wave * 64) * 16u);
         if (wave == 0 && lane < kMuU4) dma16_async(vsrc + SLAB_U4, (uint32_t)lane * 16u, dst + (uint32_t)SLAB_U4 * 16u);
     };
     if (prefetch) issue_slab(0, 0);
@@ -277,24 +278,48 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
     }
 }
 
-// One kernel per variant (TT token tiles per wave, NCT coordinate tiles): narrow plans (up to 320
-// padded coordinates) run two workgroups per compute unit, wide ones get the whole register file
-// (two token tiles per wave up to 768 padded coordinates, one beyond).  A batched launch serves only
-// the jobs whose plan uses its variant.  The tile loop is persistent.  With a non-zero
-// a.dec_ring_off the ring sits behind the record image and each tile's records are fetched during
-// the previous tile's sweep; with offset 0 they share the space and the records are fetched at the
-// tile's start.
-// (must agree with the host's variant table)
-template <int TT, int NCT> constexpr int dec_wgs_per_cu() { return NCT <= 4 ? 3 : (NCT <= 10 ? 2 : 1); }
+// One kernel per register class (TT token tiles per wave, plans of up to CLS coordinate tiles): up to 4 tiles
+// three workgroups share a compute unit, up to 10 two, up to 18 and up to 24 one with the whole register
+// file (two token tiles per wave), beyond that one token tile per wave.  Inside a class every tile runs the
+// code of its own plan's width (a switch over the widths built for the class -- their register needs are
+// alike, so the class allocates what its widest member needs and no more), which makes a batch whose plans
+// differ in width ONE launch per class: separate launches per width each ended with compute units idle
+// while their last tiles finished (the 32-layer cache at 16x has plans of 7, 8 and 9 tiles: 1.39 ms in
+// three launches, against 16 full rounds of tiles in one).  A batched launch serves only the jobs whose
+// plan belongs to its class.  The tile loop is persistent.  With a non-zero a.dec_ring_off the ring sits
+// behind the record image and each tile's records are fetched during the previous tile's sweep; with
+// offset 0 they share the space and the records are fetched at the tile's start.
+// (must agree with the host's class table)
+template <int TT, int CLS> constexpr int dec_wgs_per_cu() { return CLS <= 4 ? 3 : (CLS <= 10 ? 2 : 1); }
 
-template <typename OT, int TT, int NCT>
-__global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, NCT>())) kvtc_decode_kernel(const KernelArgs a) {
+// The widths built for each class; a plan's tile count is rounded up to the next of them at plan creation.
+template <int CLS, int TT, typename OT>
+__device__ __forceinline__ void decode_tile_of_class(const PlanDec& P, const TileRef& tr, const KernelArgs& a, uint4* work, uint4* ring,
+                                                     bool prefetch, bool has_next, const TileRef& next, const PlanDec& Pn) {
+#define KVTC_W(N) case N: decode_tile<N, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break;
+    if constexpr (CLS == 4) {
+        switch (P.dec_nct) { KVTC_W(2) default: decode_tile<4, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
+    } else if constexpr (CLS == 10) {
+        switch (P.dec_nct) { KVTC_W(6) KVTC_W(7) KVTC_W(8) KVTC_W(9) default: decode_tile<10, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
+    } else if constexpr (CLS == 18) {
+        switch (P.dec_nct) { KVTC_W(12) KVTC_W(16) KVTC_W(17) default: decode_tile<18, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
+    } else if constexpr (CLS == 24) {
+        switch (P.dec_nct) { KVTC_W(20) default: decode_tile<24, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
+    } else {
+        decode_tile<32, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn);
+    }
+#undef KVTC_W
+}
+
+template <typename OT, int TT, int CLS>
+__global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, CLS>())) kvtc_decode_kernel(const KernelArgs a) {
     extern __shared__ uint4 smem[];
     uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
     uint4* work = smem + kJobTableBytes / 16 + 1;
-    const uint32_t total = build_tile_table<false>(a, TT * 100 + NCT, tile_start, reinterpret_cast<uint32_t*>(work));
-    uint32_t tile = blockIdx.x;
-    if (tile >= total) return;
+    const uint32_t total = build_tile_table<false>(a, TT * 100 + CLS, tile_start, reinterpret_cast<uint32_t*>(work));
+    const TileRange mine = my_tiles(total);
+    uint32_t tile = mine.first;
+    if (tile >= mine.end) return;
     const bool prefetch = a.dec_ring_off != 0u;
     uint4* ring = work + a.dec_ring_off / 16u;
     TileRef tr = find_tile(a, tile_start, tile);
@@ -304,8 +329,8 @@ __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, NCT>())) kvtc_de
     wait_vmem<0>();
     __syncthreads();
     for (;;) {
-        const uint32_t next = tile + gridDim.x;
-        const bool has_next = next < total;
+        const uint32_t next = tile + mine.step;
+        const bool has_next = next < mine.end;
         TileRef trn = tr;
         PlanDec Pn = P;
         if (has_next) {
@@ -313,7 +338,7 @@ __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, NCT>())) kvtc_de
             Pn = load_plan_dec(a.plans + trn.plan);
             Pn.dec_tok_wg = 4 * 32 * TT;
         }
-        decode_tile<NCT, TT, OT>(P, tr, a, work, ring, prefetch, has_next && prefetch, trn, Pn);
+        decode_tile_of_class<CLS, TT, OT>(P, tr, a, work, ring, prefetch, has_next && prefetch, trn, Pn);
         if (!has_next) break;
         tile = next;
         tr = trn;
@@ -326,21 +351,19 @@ __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, NCT>())) kvtc_de
     }
 }
 
-// (token tiles per wave, coordinate tiles): the bulk variants, then the same widths with one token tile
-// per wave (128-token workgroup tiles) for single tensors short enough to run all their tiles at once --
-// a workgroup without a neighbour is bound by its own instruction stream, and this halves it
-#define KVTC_DEC_VARIANTS(X)                                                                                   \
-    X(2, 2) X(2, 4) X(2, 6) X(2, 8) X(2, 10) X(2, 12) X(2, 16) X(2, 18) X(2, 20) X(2, 24) X(1, 32)              \
-    X(1, 2) X(1, 4) X(1, 6) X(1, 8) X(1, 10) X(1, 12) X(1, 16) X(1, 18) X(1, 20) X(1, 24)
+// (token tiles per wave, class): the bulk kernels, then the same classes with one token tile per wave (128-token
+// workgroup tiles) for single tensors short enough to run all their tiles at once -- a workgroup without a
+// neighbour is bound by its own instruction stream, and this halves it
+#define KVTC_DEC_VARIANTS(X) X(2, 4) X(2, 10) X(2, 18) X(2, 24) X(1, 32) X(1, 4) X(1, 10) X(1, 18) X(1, 24)
 
-// key = 100 * TT + NCT
+// key = 100 * TT + CLS
 hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int key, int grid, size_t lds_bytes, hipStream_t stream) {
     const void* fn = nullptr;
     switch (key) {
-#define KVTC_X(TT, NCT)                                                                                        \
-    case (TT) * 100 + (NCT):                                                                                   \
-        fn = dtype == KVTC_BF16 ? reinterpret_cast<const void*>(&kvtc_decode_kernel<uint16_t, TT, NCT>)        \
-                                : reinterpret_cast<const void*>(&kvtc_decode_kernel<float, TT, NCT>);          \
+#define KVTC_X(TT, CLS)                                                                                        \
+    case (TT) * 100 + (CLS):                                                                                   \
+        fn = dtype == KVTC_BF16 ? reinterpret_cast<const void*>(&kvtc_decode_kernel<uint16_t, TT, CLS>)        \
+                                : reinterpret_cast<const void*>(&kvtc_decode_kernel<float, TT, CLS>);          \
         break;
         KVTC_DEC_VARIANTS(KVTC_X)
 #undef KVTC_X

@@ -391,7 +391,8 @@ __global__ void __launch_bounds__(NW * 64, (enc_wgs_per_cu<WC, NTW, NW>())) kvtc
     uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
     uint4* work = smem + kJobTableBytes / 16 + 1;
     const uint32_t total = build_tile_table<true, NW * 64>(a, NW * 10000 + WC * 100 + NTW, tile_start, reinterpret_cast<uint32_t*>(work));
-    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
+    const TileRange mine = my_tiles(total);
+    for (uint32_t tile = mine.first; tile < mine.end; tile += mine.step) {
         const TileRef tr = find_tile(a, tile_start, tile);
         const PlanEnc P = load_plan_enc(a.plans + tr.plan);
         encode_tile<NTW, WC, XT, NW>(P, tr, a, work);
