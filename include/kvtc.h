@@ -218,6 +218,32 @@ kvtc_status kvtc_fp8_unpack(const void* in_dev, size_t in_bytes, int64_t n_token
                             void* x_out_dev, kvtc_dtype dtype, int64_t ld_x, kvtc_stream stream);
 
 /*
+ * ---- Positional rotation of keys ----------------------------------------------------------
+ * (paper, Section "Feature decorrelation": the rotary positional embedding is removed from keys
+ * before they are transform-coded, because it hides their low-rank structure, and decoded keys are
+ * rotated again.)  kvtc_rope rotates a key tensor in place: inside every head the features are
+ * paired, and the pair (a, b) of the token at position m becomes
+ *     a' = a cos(m theta_j) - b sin(m theta_j),  b' = a sin(m theta_j) + b cos(m theta_j),
+ *     theta_j = base^(-2 j / d_head),  j = 0 .. d_head/2 - 1;
+ * inverse = 1 turns by the opposite angle (undoes it).  A cache of rotated keys is coded as
+ * kvtc_rope(inverse = 1) then kvtc_encode, and read back as kvtc_decode then kvtc_rope(inverse = 0).
+ *   x_dev           element (token t, head h, feature f) at x_dev[t * token_stride + h * head_stride + f];
+ *                   token-major tensors [T][H * d_head] have head_stride = d_head, head-major caches
+ *                   [H][T][d_head] have token_stride = d_head and head_stride = T * d_head.  Overlapping
+ *                   strides give KVTC_E_ARG.  d_head even, at most 256.
+ *   positions_dev   NULL (token t sits at position0 + t) or a device array of n_tokens positions
+ *   pairing         which features form pair j: a convention of the model's code, not of the method
+ * Angles, sines, cosines and the rotation are computed in double precision and the result is rounded
+ * once (nearest even) to dtype.  Ordered on `stream`, allocates nothing, does not synchronise;
+ * n_tokens == 0 is a no-op.
+ */
+typedef enum { KVTC_ROPE_HALF = 0 /* (j, j + d_head/2) */, KVTC_ROPE_INTERLEAVED = 1 /* (2j, 2j + 1) */ } kvtc_rope_pairing;
+kvtc_status kvtc_rope(void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int n_heads, int d_head,
+                      int64_t token_stride, int64_t head_stride, const int32_t* positions_dev,
+                      int64_t position0, double base, kvtc_rope_pairing pairing, int inverse,
+                      kvtc_stream stream);
+
+/*
  * Stream offsets for appending to caches that each own a region of the stream buffer, computed on
  * the GPU:  offsets_dev[j] = region_dev[j] + n_coded_dev[j] * R(plan of job j),  j < n_jobs, and
  * offsets_dev[n_jobs] = region_dev[n_jobs].  region_dev has n_jobs + 1 ascending entries (byte

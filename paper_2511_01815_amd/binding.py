@@ -74,6 +74,8 @@ def lib() -> C.CDLL:
         L.kvtc_fp8_pack.argtypes = [vp, C.c_int, i64, C.c_int, i64, vp, sz, vp]
         L.kvtc_fp8_unpack.argtypes = [vp, sz, i64, C.c_int, vp, C.c_int, i64, vp]
         L.kvtc_offsets_append.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp]
+        L.kvtc_rope.argtypes = [vp, C.c_int, i64, C.c_int, C.c_int, i64, i64, vp, i64, C.c_double, C.c_int, C.c_int, vp]
+        L.kvtc_rope.restype = C.c_int
         L.kvtc_last_error.argtypes = []
         L.kvtc_last_error.restype = C.c_char_p
         L.kvtc_host_f16_round_down.argtypes = [C.c_float]
@@ -211,6 +213,16 @@ def kvtc_offsets_append(batch: int, jobs_dev, n_jobs: int, region_dev, n_coded_d
 
 
 PROBE_READ, PROBE_WRITE, PROBE_COPY = 0, 1, 2
+
+
+ROPE_HALF, ROPE_INTERLEAVED = 0, 1
+
+
+def kvtc_rope(x_dev, dtype: int, n_tokens: int, n_heads: int, d_head: int, token_stride: int, head_stride: int,
+              positions_dev, position0: int, base: float, pairing: int, inverse: bool, stream=None) -> None:
+    _check(lib().kvtc_rope(_ptr(x_dev), dtype, n_tokens, n_heads, d_head, token_stride, head_stride,
+                           _ptr(positions_dev) if positions_dev is not None else None, position0, float(base), pairing,
+                           1 if inverse else 0, _stream(stream)))
 
 
 def kvtc_probe_stream(mode: int, src_dev, dst_dev, nbytes: int, stream=None) -> None:

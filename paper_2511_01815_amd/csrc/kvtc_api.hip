@@ -23,6 +23,15 @@ hipError_t launch_fp8_pack(const void* x, kvtc_dtype dtype, int64_t n_tokens, in
 hipError_t launch_fp8_unpack(const void* in, int64_t n_tokens, int p, void* x, kvtc_dtype dtype, int64_t ld_x, hipStream_t stream);
 hipError_t launch_offsets_append(const uint32_t* rec_dwords, int n_plans, const kvtc_job* jobs, int n_jobs, const uint64_t* region,
                                  const int64_t* n_coded, uint64_t* offsets, hipStream_t stream);
+struct RopeArgs {
+    void* x;
+    int64_t n_tokens, token_stride, head_stride;
+    const int32_t* positions;
+    int64_t position0;
+    int32_t n_heads, d_head, inverse;
+    double theta[128];
+};
+hipError_t launch_rope(const RopeArgs& a, kvtc_dtype dtype, int interleaved, int grid, hipStream_t stream);
 int decode_rec_bytes(int tt, int rec_dwords);
 int decode_ring_bytes(int nct);
 int decode_stage_u4(int nct);
@@ -632,6 +641,44 @@ kvtc_status kvtc_window_split(int64_t ctx, int s, int w, int c, kvtc_split* out)
 }
 
 double kvtc_cr_with_window(double ctx, double w, double s, double cr) { return ctx / ((ctx - w - s) / cr + w + s / 2.0); }
+
+kvtc_status kvtc_rope(void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int n_heads, int d_head, int64_t token_stride,
+                      int64_t head_stride, const int32_t* positions_dev, int64_t position0, double base, kvtc_rope_pairing pairing,
+                      int inverse, kvtc_stream stream) {
+    if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_rope: n_tokens=%lld", (long long)n_tokens);
+    if (n_heads < 1 || d_head < 2 || (d_head & 1) || d_head > 256)
+        return fail(KVTC_E_ARG, "kvtc_rope: need n_heads >= 1 and an even d_head in 2..256 (n_heads=%d d_head=%d)", n_heads, d_head);
+    if (!dtype_ok(dtype)) return fail(KVTC_E_ARG, "kvtc_rope: unknown dtype %d", (int)dtype);
+    if (pairing != KVTC_ROPE_HALF && pairing != KVTC_ROPE_INTERLEAVED) return fail(KVTC_E_ARG, "kvtc_rope: unknown pairing %d", (int)pairing);
+    if (!(base > 0.0) || !std::isfinite(base)) return fail(KVTC_E_ARG, "kvtc_rope: base must be positive and finite");
+    if (inverse != 0 && inverse != 1) return fail(KVTC_E_ARG, "kvtc_rope: inverse must be 0 or 1");
+    if (n_tokens == 0) return KVTC_OK;
+    if (!x_dev) return fail(KVTC_E_ARG, "kvtc_rope: null buffer");
+    // heads and tokens must not overlap: either tokens-major (a token's heads inside its row) or heads-major (a head's tokens inside its slab)
+    const bool tokens_major = head_stride >= d_head && token_stride >= (int64_t)(n_heads - 1) * head_stride + d_head;
+    const bool heads_major = token_stride >= d_head && head_stride >= (n_tokens - 1) * token_stride + d_head;
+    if (!tokens_major && !heads_major)
+        return fail(KVTC_E_ARG, "kvtc_rope: strides (token %lld, head %lld) let elements overlap", (long long)token_stride, (long long)head_stride);
+    if (reinterpret_cast<uintptr_t>(x_dev) % elem_size(dtype) != 0) return fail(KVTC_E_ARG, "kvtc_rope: misaligned buffer");
+    RopeArgs a;
+    memset(&a, 0, sizeof(a));
+    a.x = x_dev;
+    a.n_tokens = n_tokens;
+    a.token_stride = token_stride;
+    a.head_stride = head_stride;
+    a.positions = positions_dev;
+    a.position0 = position0;
+    a.n_heads = n_heads;
+    a.d_head = d_head;
+    a.inverse = inverse;
+    for (int j = 0; j < d_head / 2; ++j) a.theta[j] = std::pow(base, -2.0 * (double)j / (double)d_head);
+    const int64_t items = n_tokens * (int64_t)(d_head / 2);
+    const int64_t want = (items + 255) / 256;
+    const int64_t cap = (int64_t)cu_count() * 16;
+    hipError_t e = launch_rope(a, dtype, pairing == KVTC_ROPE_INTERLEAVED, (int)(want < cap ? want : cap), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_rope: launch failed: %s", hipGetErrorString(e));
+    return KVTC_OK;
+}
 
 kvtc_status kvtc_fp8_pack(const void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int p, int64_t ld_x, void* out_dev, size_t out_cap,
                           kvtc_stream stream) {

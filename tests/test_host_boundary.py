@@ -149,6 +149,29 @@ def test_fp8_entry_points_reject_bad_arguments_before_any_launch():
     assert L.kvtc_offsets_append(None, None, 0, None, None, None, None) == 1
 
 
+def test_rope_rejects_bad_arguments_before_any_launch():
+    L = kv.lib()
+    buf = np.zeros(4096, dtype=np.uint8)
+    ptr = buf.ctypes.data & ~15
+    ok = dict(dtype=0, T=4, H=8, d=128, ts=1024, hs=128)
+
+    def call(x=ptr, dtype=0, T=4, H=8, d=128, ts=1024, hs=128, base=10000.0, pairing=0, inverse=0):
+        return L.kvtc_rope(x, dtype, T, H, d, ts, hs, None, 0, base, pairing, inverse, None)
+
+    assert call(x=None, T=0) == 0                      # nothing to do
+    assert call(x=None) == 1                           # null buffer
+    assert call(dtype=5) == 1
+    assert call(d=127) == 1 and call(d=0) == 1 and call(d=258) == 1
+    assert call(H=0) == 1
+    assert call(ts=1023) == 1                          # a token's heads would run into the next token
+    assert call(ts=128, hs=3 * 128) == 1               # heads-major, but a head's slab is shorter than its tokens
+    assert call(base=0.0) == 1 and call(base=float("inf")) == 1
+    assert call(pairing=2) == 1 and call(inverse=2) == 1
+    assert call(T=-1) == 1
+    assert "kvtc_rope" in kv.kvtc_last_error()
+    del ok
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
