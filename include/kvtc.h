@@ -218,6 +218,37 @@ kvtc_status kvtc_fp8_unpack(const void* in_dev, size_t in_bytes, int64_t n_token
                             void* x_out_dev, kvtc_dtype dtype, int64_t ld_x, kvtc_stream stream);
 
 /*
+ * ---- Features that are not contiguous in memory ------------------------------------------
+ * A token's p features may come in blocks that lie apart: the heads of a cache kept as
+ * [heads][tokens][d_head], or the per-layer tensors [layers][tokens][1024] whose concatenation a
+ * cross-layer basis transforms (paper, Section "Feature decorrelation": keys or values of several
+ * layers and heads are concatenated before the PCA).  Feature f of token t sits at
+ *     x[t * token_stride + (f / block_features) * block_stride + f % block_features]     (elements).
+ *   block_features   0: contiguous features (then this is the ld_x of the plain calls); else a power
+ *                    of two >= 64 that divides p
+ *   token_stride     >= block_features (>= p when contiguous), at most 2^21
+ *   block_stride     >= block_features
+ * Base and both strides 16-byte aligned.  Blocks must lie inside a token's row or tokens inside a
+ * block's slab (anything else overlaps: KVTC_E_ARG; a batched call cannot see the token counts and
+ * checks block_stride >= token_stride only).  The _blocked calls are the plain calls with a layout in
+ * place of ld_x; everything else is as documented there.  In a batched call x_row0 counts tokens
+ * (units of token_stride) from the base.
+ */
+typedef struct { int64_t token_stride; int32_t block_features; int32_t reserved; int64_t block_stride; } kvtc_layout;
+kvtc_status kvtc_encode_blocked(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens,
+                                const kvtc_layout* layout, void* out_dev, size_t out_cap, kvtc_stream stream);
+kvtc_status kvtc_decode_blocked(const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens,
+                                void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream);
+kvtc_status kvtc_encode_batch_blocked(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs,
+                                      const void* x_base_dev, kvtc_dtype dtype, const kvtc_layout* layout,
+                                      const uint64_t* offsets_dev, void* out_base_dev, size_t out_cap,
+                                      uint32_t* status_dev, kvtc_stream stream);
+kvtc_status kvtc_decode_batch_blocked(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs,
+                                      const void* in_base_dev, size_t in_bytes, const uint64_t* offsets_dev,
+                                      void* x_out_base_dev, kvtc_dtype dtype, const kvtc_layout* layout,
+                                      uint32_t* status_dev, kvtc_stream stream);
+
+/*
  * ---- Positional rotation of keys ----------------------------------------------------------
  * (paper, Section "Feature decorrelation": the rotary positional embedding is removed from keys
  * before they are transform-coded, because it hides their low-rank structure, and decoded keys are

@@ -28,6 +28,10 @@ class KvtcSplit(C.Structure):
     _fields_ = [("n_sink", C.c_int64), ("n_coded", C.c_int64), ("n_window", C.c_int64)]
 
 
+class KvtcLayout(C.Structure):
+    _fields_ = [("token_stride", C.c_int64), ("block_features", C.c_int32), ("reserved", C.c_int32), ("block_stride", C.c_int64)]
+
+
 def lib_path() -> str:
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvtc.so")
 
@@ -74,6 +78,13 @@ def lib() -> C.CDLL:
         L.kvtc_fp8_pack.argtypes = [vp, C.c_int, i64, C.c_int, i64, vp, sz, vp]
         L.kvtc_fp8_unpack.argtypes = [vp, sz, i64, C.c_int, vp, C.c_int, i64, vp]
         L.kvtc_offsets_append.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp]
+        lp = C.POINTER(KvtcLayout)
+        L.kvtc_encode_blocked.argtypes = [vp, vp, C.c_int, i64, lp, vp, sz, vp]
+        L.kvtc_decode_blocked.argtypes = [vp, vp, sz, i64, vp, C.c_int, lp, vp]
+        L.kvtc_encode_batch_blocked.argtypes = [vp, vp, C.c_int, vp, C.c_int, lp, vp, vp, sz, vp, vp]
+        L.kvtc_decode_batch_blocked.argtypes = [vp, vp, C.c_int, vp, sz, vp, vp, C.c_int, lp, vp, vp]
+        for f in (L.kvtc_encode_blocked, L.kvtc_decode_blocked, L.kvtc_encode_batch_blocked, L.kvtc_decode_batch_blocked):
+            f.restype = C.c_int
         L.kvtc_rope.argtypes = [vp, C.c_int, i64, C.c_int, C.c_int, i64, i64, vp, i64, C.c_double, C.c_int, C.c_int, vp]
         L.kvtc_rope.restype = C.c_int
         L.kvtc_last_error.argtypes = []
@@ -216,6 +227,31 @@ PROBE_READ, PROBE_WRITE, PROBE_COPY = 0, 1, 2
 
 
 ROPE_HALF, ROPE_INTERLEAVED = 0, 1
+
+
+def layout(token_stride: int, block_features: int = 0, block_stride: int = 0) -> "KvtcLayout":
+    """A kvtc_layout: feature f of token t at t * token_stride + (f // block_features) * block_stride + f % block_features."""
+    return KvtcLayout(token_stride, block_features, 0, block_stride)
+
+
+def kvtc_encode_blocked(plan, x_dev, dtype: int, n_tokens: int, lay, out_dev, out_cap: int, stream=None) -> None:
+    _check(lib().kvtc_encode_blocked(plan, _ptr(x_dev), dtype, n_tokens, C.byref(lay), _ptr(out_dev), out_cap, _stream(stream)))
+
+
+def kvtc_decode_blocked(plan, in_dev, in_bytes: int, n_tokens: int, x_out_dev, dtype: int, lay, stream=None) -> None:
+    _check(lib().kvtc_decode_blocked(plan, _ptr(in_dev), in_bytes, n_tokens, _ptr(x_out_dev), dtype, C.byref(lay), _stream(stream)))
+
+
+def kvtc_encode_batch_blocked(batch, jobs_dev, n_jobs: int, x_base_dev, dtype: int, lay, offsets_dev, out_base_dev,
+                              out_cap: int, status_dev, stream=None) -> None:
+    _check(lib().kvtc_encode_batch_blocked(batch, _ptr(jobs_dev), n_jobs, _ptr(x_base_dev), dtype, C.byref(lay), _ptr(offsets_dev),
+                                           _ptr(out_base_dev), out_cap, _ptr(status_dev), _stream(stream)))
+
+
+def kvtc_decode_batch_blocked(batch, jobs_dev, n_jobs: int, in_base_dev, in_bytes: int, offsets_dev, x_out_base_dev,
+                              dtype: int, lay, status_dev, stream=None) -> None:
+    _check(lib().kvtc_decode_batch_blocked(batch, _ptr(jobs_dev), n_jobs, _ptr(in_base_dev), in_bytes, _ptr(offsets_dev),
+                                           _ptr(x_out_base_dev), dtype, C.byref(lay), _ptr(status_dev), _stream(stream)))
 
 
 def kvtc_rope(x_dev, dtype: int, n_tokens: int, n_heads: int, d_head: int, token_stride: int, head_stride: int,

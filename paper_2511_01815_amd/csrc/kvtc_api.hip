@@ -58,6 +58,7 @@ struct kvtc_batch {
     std::vector<EncVariant> enc_short;                  // the short-job variants among the plans (64-token tiles)
     std::vector<DecVariant> dec;
     int max_p;
+    std::vector<int32_t> ps;                            // the distinct feature counts among the plans
     std::vector<int32_t> rec_dwords;
     uint32_t* rec_dwords_dev;
 };
@@ -439,13 +440,74 @@ static kvtc_status check_x(const char* who, const void* x, kvtc_dtype dtype, int
     return KVTC_OK;
 }
 
+// A feature layout as the kernels take it: token stride, log2 of the block size (0 = contiguous features), and the
+// gap between a block's end and the token's next block.
+struct XLayout { int64_t ld; int32_t blk_log2; int64_t blk_jump; };
+
+// Checks a kvtc_layout for a tensor of p features (n_tokens < 0: unknown, as in a batched call) and converts it.
+static kvtc_status check_layout(const char* who, const void* x, kvtc_dtype dtype, const kvtc_layout* lay, int p, int64_t n_tokens,
+                                XLayout* out) {
+    if (!lay) return fail(KVTC_E_ARG, "%s: null layout", who);
+    if (!dtype_ok(dtype)) return fail(KVTC_E_ARG, "%s: unknown dtype %d", who, (int)dtype);
+    const int bf = lay->block_features;
+    const int64_t ts = lay->token_stride, bs = lay->block_stride;
+    if (bf == 0) {
+        kvtc_status st = check_x(who, x, dtype, ts, p);
+        if (st != KVTC_OK) return st;
+        *out = XLayout{ts, 0, 0};
+        return KVTC_OK;
+    }
+    if (bf < 64 || (bf & (bf - 1)) != 0 || p % bf != 0)
+        return fail(KVTC_E_ARG, "%s: block_features=%d must be a power of two, at least 64, that divides p=%d", who, bf, p);
+    if (ts < bf || ts > kMaxPitch) return fail(KVTC_E_ARG, "%s: token_stride=%lld outside %d..%d", who, (long long)ts, bf, kMaxPitch);
+    if (bs < bf) return fail(KVTC_E_ARG, "%s: block_stride=%lld < block_features=%d", who, (long long)bs, bf);
+    const size_t eb = elem_size(dtype);
+    if ((reinterpret_cast<uintptr_t>(x) & 15u) || ((size_t)ts * eb) % 16 != 0 || ((size_t)bs * eb) % 16 != 0)
+        return fail(KVTC_E_ARG, "%s: feature array base, token stride and block stride must be 16-byte aligned", who);
+    // blocks inside a token's row, or tokens inside a block's slab: anything else lets elements overlap
+    const int nb = p / bf;
+    const bool tokens_major = ts >= (int64_t)(nb - 1) * bs + bf;
+    const bool blocks_major = n_tokens < 0 ? bs >= ts : bs >= (n_tokens - 1) * ts + bf;
+    if (!tokens_major && !blocks_major)
+        return fail(KVTC_E_ARG, "%s: strides (token %lld, block %lld) let elements overlap", who, (long long)ts, (long long)bs);
+    int lg = 0;
+    while ((1 << lg) < bf) ++lg;
+    *out = XLayout{ts, lg, bs - bf};
+    return KVTC_OK;
+}
+
+static kvtc_status encode_single(const char* who, const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens,
+                                 const kvtc_layout* layout, void* out_dev, size_t out_cap, kvtc_stream stream);
+static kvtc_status decode_single(const char* who, const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens,
+                                 void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream);
+
 kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int64_t ld_x,
                         void* out_dev, size_t out_cap, kvtc_stream stream) {
+    const kvtc_layout lay = {ld_x, 0, 0, 0};
+    return encode_single("kvtc_encode", plan, x_dev, dtype, n_tokens, &lay, out_dev, out_cap, stream);
+}
+kvtc_status kvtc_encode_blocked(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens,
+                                const kvtc_layout* layout, void* out_dev, size_t out_cap, kvtc_stream stream) {
+    return encode_single("kvtc_encode_blocked", plan, x_dev, dtype, n_tokens, layout, out_dev, out_cap, stream);
+}
+kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens, void* x_out_dev,
+                        kvtc_dtype dtype, int64_t ld_x, kvtc_stream stream) {
+    const kvtc_layout lay = {ld_x, 0, 0, 0};
+    return decode_single("kvtc_decode", plan, in_dev, in_bytes, n_tokens, x_out_dev, dtype, &lay, stream);
+}
+kvtc_status kvtc_decode_blocked(const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens, void* x_out_dev,
+                                kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream) {
+    return decode_single("kvtc_decode_blocked", plan, in_dev, in_bytes, n_tokens, x_out_dev, dtype, layout, stream);
+}
+
+static kvtc_status encode_single(const char* who, const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens,
+                                 const kvtc_layout* layout, void* out_dev, size_t out_cap, kvtc_stream stream) {
     if (!plan) return fail(KVTC_E_ARG, "kvtc_encode: null plan");
     if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_encode: n_tokens=%lld", (long long)n_tokens);
     if (n_tokens == 0) return KVTC_OK;
     if (!x_dev || !out_dev) return fail(KVTC_E_ARG, "kvtc_encode: null buffer");
-    kvtc_status st = check_x("kvtc_encode", x_dev, dtype, ld_x, plan->h.p);
+    XLayout xl;
+    kvtc_status st = check_layout(who, x_dev, dtype, layout, plan->h.p, n_tokens, &xl);
     if (st != KVTC_OK) return st;
     if (reinterpret_cast<uintptr_t>(out_dev) & 15u) return fail(KVTC_E_ARG, "kvtc_encode: out_dev must be 16-byte aligned");
     if (out_cap < plan->record_bytes * (size_t)n_tokens)
@@ -459,7 +521,9 @@ kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dty
     a.single = kvtc_job{0, (int32_t)n_tokens, 0};
     a.offsets = nullptr;
     a.x = x_dev;
-    a.ld_x = ld_x;
+    a.ld_x = xl.ld;
+    a.x_blk_log2 = xl.blk_log2;
+    a.x_blk_jump = xl.blk_jump;
     a.stream_buf = out_dev;
     a.cap = out_cap;
     a.status = nullptr;
@@ -480,13 +544,14 @@ kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dty
     return KVTC_OK;
 }
 
-kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens, void* x_out_dev,
-                        kvtc_dtype dtype, int64_t ld_x, kvtc_stream stream) {
+static kvtc_status decode_single(const char* who, const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens,
+                                 void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream) {
     if (!plan) return fail(KVTC_E_ARG, "kvtc_decode: null plan");
     if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_decode: n_tokens=%lld", (long long)n_tokens);
     if (n_tokens == 0) return KVTC_OK;
     if (!in_dev || !x_out_dev) return fail(KVTC_E_ARG, "kvtc_decode: null buffer");
-    kvtc_status st = check_x("kvtc_decode", x_out_dev, dtype, ld_x, plan->h.p);
+    XLayout xl;
+    kvtc_status st = check_layout(who, x_out_dev, dtype, layout, plan->h.p, n_tokens, &xl);
     if (st != KVTC_OK) return st;
     if (reinterpret_cast<uintptr_t>(in_dev) & 15u) return fail(KVTC_E_ARG, "kvtc_decode: in_dev must be 16-byte aligned");
     if (in_bytes < plan->record_bytes * (size_t)n_tokens)
@@ -498,7 +563,9 @@ kvtc_status kvtc_decode(const kvtc_plan* plan, const void* in_dev, size_t in_byt
     a.n_jobs = 1;
     a.single = kvtc_job{0, (int32_t)n_tokens, 0};
     a.x = x_out_dev;
-    a.ld_x = ld_x;
+    a.ld_x = xl.ld;
+    a.x_blk_log2 = xl.blk_log2;
+    a.x_blk_jump = xl.blk_jump;
     a.stream_buf = const_cast<void*>(in_dev);
     a.cap = in_bytes;
     const int slots = cu_count() * plan->h.dec_wgs;
@@ -577,6 +644,11 @@ kvtc_status kvtc_batch_create(kvtc_batch** out, const kvtc_plan* const* plans, i
             if (ph.dec_ring_lds > v->ring) v->ring = ph.dec_ring_lds;
         }
         if (ph.p > b->max_p) b->max_p = ph.p;
+        {
+            bool seen = false;
+            for (int v : b->ps) seen = seen || v == ph.p;
+            if (!seen) b->ps.push_back(ph.p);
+        }
     }
     } catch (const std::bad_alloc&) {
         delete b;
@@ -707,18 +779,19 @@ kvtc_status kvtc_fp8_unpack(const void* in_dev, size_t in_bytes, int64_t n_token
 }
 
 static kvtc_status batch_common(const char* who, const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs,
-                                const void* x, kvtc_dtype dtype, int64_t ld_x, const uint64_t* offsets_dev,
-                                const void* stream_buf, const uint32_t* status_dev, bool* nothing) {
+                                const void* x, kvtc_dtype dtype, const kvtc_layout* layout, const uint64_t* offsets_dev,
+                                const void* stream_buf, const uint32_t* status_dev, bool* nothing, XLayout* xl) {
     *nothing = false;
     if (!batch) return fail(KVTC_E_ARG, "%s: null batch", who);
     if (n_jobs < 0) return fail(KVTC_E_ARG, "%s: n_jobs=%d", who, n_jobs);
     if (n_jobs == 0) { *nothing = true; return KVTC_OK; }
     if (n_jobs > kMaxJobs) return fail(KVTC_E_UNSUPPORTED, "%s: %d jobs, at most %d per call", who, n_jobs, kMaxJobs);
     if (!jobs_dev || !x || !offsets_dev || !stream_buf || !status_dev) return fail(KVTC_E_ARG, "%s: null buffer", who);
-    if (!dtype_ok(dtype)) return fail(KVTC_E_ARG, "%s: unknown dtype %d", who, (int)dtype);
-    if ((reinterpret_cast<uintptr_t>(x) & 15u) || ((size_t)ld_x * elem_size(dtype)) % 16 != 0 || ld_x <= 0)
-        return fail(KVTC_E_ARG, "%s: feature array base and row pitch must be 16-byte aligned", who);
-    if (ld_x > kMaxPitch) return fail(KVTC_E_ARG, "%s: ld_x=%lld above %d", who, (long long)ld_x, kMaxPitch);
+    if (!layout) return fail(KVTC_E_ARG, "%s: null layout", who);
+    for (int pv : batch->ps) {                         // the layout must suit every plan of the batch
+        kvtc_status st = check_layout(who, x, dtype, layout, pv, -1, xl);
+        if (st != KVTC_OK) return st;
+    }
     if (reinterpret_cast<uintptr_t>(stream_buf) & 15u) return fail(KVTC_E_ARG, "%s: stream buffer must be 16-byte aligned", who);
     return KVTC_OK;
 }
@@ -726,10 +799,19 @@ static kvtc_status batch_common(const char* who, const kvtc_batch* batch, const 
 kvtc_status kvtc_encode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs, const void* x_base_dev,
                               kvtc_dtype dtype, int64_t ld_x, const uint64_t* offsets_dev, void* out_base_dev,
                               size_t out_cap, uint32_t* status_dev, kvtc_stream stream) {
+    const kvtc_layout lay = {ld_x, 0, 0, 0};
+    return kvtc_encode_batch_blocked(batch, jobs_dev, n_jobs, x_base_dev, dtype, &lay, offsets_dev, out_base_dev, out_cap, status_dev, stream);
+}
+
+kvtc_status kvtc_encode_batch_blocked(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs, const void* x_base_dev,
+                                      kvtc_dtype dtype, const kvtc_layout* layout, const uint64_t* offsets_dev, void* out_base_dev,
+                                      size_t out_cap, uint32_t* status_dev, kvtc_stream stream) {
     bool nothing;
-    kvtc_status st = batch_common("kvtc_encode_batch", batch, jobs_dev, n_jobs, x_base_dev, dtype, ld_x, offsets_dev,
-                                  out_base_dev, status_dev, &nothing);
+    XLayout xl = {0, 0, 0};
+    kvtc_status st = batch_common("kvtc_encode_batch", batch, jobs_dev, n_jobs, x_base_dev, dtype, layout, offsets_dev,
+                                  out_base_dev, status_dev, &nothing, &xl);
     if (st != KVTC_OK || nothing) return st;
+    const int64_t ld_x = xl.ld;
     KernelArgs a;
     memset(&a, 0, sizeof(a));
     a.plans = batch->plans_dev;
@@ -739,10 +821,11 @@ kvtc_status kvtc_encode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.offsets = offsets_dev;
     a.x = x_base_dev;
     a.ld_x = ld_x;
+    a.x_blk_log2 = xl.blk_log2;
+    a.x_blk_jump = xl.blk_jump;
     a.stream_buf = out_base_dev;
     a.cap = out_cap;
     a.status = status_dev;
-    if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_encode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
     // Jobs of at most one 64-token tile go to their plan's short-job variant (one small launch per such
     // variant: a short job is one workgroup), the rest to the bulk variants.
     a.enc_short_max = kEncShortTile;
@@ -839,10 +922,19 @@ kvtc_status kvtc_encode_batch_static(const kvtc_plan* const* plans, int n_plans,
 kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs, const void* in_base_dev,
                               size_t in_bytes, const uint64_t* offsets_dev, void* x_out_base_dev, kvtc_dtype dtype,
                               int64_t ld_x, uint32_t* status_dev, kvtc_stream stream) {
+    const kvtc_layout lay = {ld_x, 0, 0, 0};
+    return kvtc_decode_batch_blocked(batch, jobs_dev, n_jobs, in_base_dev, in_bytes, offsets_dev, x_out_base_dev, dtype, &lay, status_dev, stream);
+}
+
+kvtc_status kvtc_decode_batch_blocked(const kvtc_batch* batch, const kvtc_job* jobs_dev, int n_jobs, const void* in_base_dev,
+                                      size_t in_bytes, const uint64_t* offsets_dev, void* x_out_base_dev, kvtc_dtype dtype,
+                                      const kvtc_layout* layout, uint32_t* status_dev, kvtc_stream stream) {
     bool nothing;
-    kvtc_status st = batch_common("kvtc_decode_batch", batch, jobs_dev, n_jobs, x_out_base_dev, dtype, ld_x, offsets_dev,
-                                  in_base_dev, status_dev, &nothing);
+    XLayout xl = {0, 0, 0};
+    kvtc_status st = batch_common("kvtc_decode_batch", batch, jobs_dev, n_jobs, x_out_base_dev, dtype, layout, offsets_dev,
+                                  in_base_dev, status_dev, &nothing, &xl);
     if (st != KVTC_OK || nothing) return st;
+    const int64_t ld_x = xl.ld;
     KernelArgs a;
     memset(&a, 0, sizeof(a));
     a.plans = batch->plans_dev;
@@ -852,10 +944,11 @@ kvtc_status kvtc_decode_batch(const kvtc_batch* batch, const kvtc_job* jobs_dev,
     a.offsets = offsets_dev;
     a.x = x_out_base_dev;
     a.ld_x = ld_x;
+    a.x_blk_log2 = xl.blk_log2;
+    a.x_blk_jump = xl.blk_jump;
     a.stream_buf = const_cast<void*>(in_base_dev);
     a.cap = in_bytes;
     a.status = status_dev;
-    if (ld_x < batch->max_p) return fail(KVTC_E_ARG, "kvtc_decode_batch: ld_x=%lld < p=%d", (long long)ld_x, batch->max_p);
     for (const auto& v : batch->dec) {
         const DecLayout lay = decode_layout(v.rec, v.ring, v.wgs);
         a.dec_ring_off = lay.ring_off;

@@ -258,7 +258,10 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
         if (more) issue_slab(f0 + 2, 0);
         tile_step(1, acc1);
         {
-            char* ob = obase + (size_t)(f0 / 2) * (64 * sizeof(OT));
+            // the 64-feature span f0 / 2 of the token's features; with a blocked layout (heads or layers apart in
+            // memory) every whole block before it adds the gap between blocks
+            char* ob = obase + (size_t)(f0 / 2) * (64 * sizeof(OT)) +
+                       (a.x_blk_log2 ? (size_t)(((f0 / 2) * 64) >> a.x_blk_log2) * ((size_t)a.x_blk_jump * sizeof(OT)) : (size_t)0);
             // (through an empty asm so that the 16*TT offsets are recomputed here -- three vector
             // instructions each -- instead of being hoisted out of the sweep into registers the
             // accumulators need)

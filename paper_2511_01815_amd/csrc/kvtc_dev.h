@@ -65,6 +65,8 @@ struct KernelArgs {
     const uint64_t* offsets;   // device, [n_jobs + 1], or nullptr (single job at offset 0)
     const void* x;             // feature array (encode: input, decode: output)
     int64_t ld_x;
+    int32_t x_blk_log2;        // 0: a token's features are contiguous.  Else they come in blocks of 2^x_blk_log2 features (a head, a layer) ...
+    int64_t x_blk_jump;        // ... and x_blk_jump elements lie between the end of a block and the start of the token's next one
     void* stream_buf;          // record stream (encode: output, decode: input)
     uint64_t cap;              // bytes available in stream_buf
     uint32_t* status;          // device, may be nullptr

@@ -178,8 +178,13 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
     // All global traffic of the main loop is asynchronous global->LDS transfers issued
     // NSTAGE-1 steps ahead; the only wait is the one in front of the barrier that publishes
     // the next stage, and it leaves the younger stages in flight.
+    // byte offset of slab s inside a token's features: KS * 16 features per slab; with a blocked layout
+    // (heads or layers apart in memory) every whole block before it adds the gap between blocks
+    const int blk_lg = a.x_blk_log2;
+    const size_t blk_jump_b = (size_t)a.x_blk_jump * sizeof(XT);
     auto issue = [&](int s, int stage) {
         const uint32_t base = lds_ring + stage * STAGE_B;
+        const size_t xoff = (size_t)s * XS::ROW_B + (blk_lg ? (size_t)((s * (16 * KS)) >> blk_lg) * blk_jump_b : (size_t)0);
         const uint4* vsrc = vg + (size_t)s * SLAB_U4 + wave * 64 + lane;
 #pragma unroll
         for (int i = 0; i < NV; ++i)
@@ -188,7 +193,7 @@ __device__ __forceinline__ void encode_tile(const PlanEnc& P, const TileRef& tr,
 #pragma unroll
         for (int j = 0; j < NXD; ++j)
             if (j * NW + wave < NX_TOTAL)
-                dma16_async(xsrc[j] + (size_t)s * XS::ROW_B, __builtin_amdgcn_readfirstlane(base + xdst[j]));
+                dma16_async(xsrc[j] + xoff, __builtin_amdgcn_readfirstlane(base + xdst[j]));
     };
     auto compute = [&](int stage) {
         const uint4* abase = reinterpret_cast<const uint4*>(ring + stage * STAGE_B) + (wc * NTW) * 64 + lane;
