@@ -186,5 +186,13 @@ def ragged_lengths(workload: str, layer: int = 0) -> np.ndarray:
     return np.clip(np.rint(np.exp(u)), lo, hi).astype(np.int64)
 
 
+
+def cross_layer_spec(n_layers: int, alpha: float = 1.0) -> LayerSpec:
+    """The features of n_layers 8B-shaped layers (1024 each) side by side, correlated across layers: the recipe
+    above over all n_layers * 1024 features at once (one spectrum, one rotation, a few outlier channels).  Stands in
+    for the concatenated keys or values of several layers, whose cross-layer redundancy a single basis exploits
+    (paper, Section "Feature decorrelation"; appendix "PCA feature concat size vs performance")."""
+    return LayerSpec(p=1024 * n_layers, alpha=alpha, seed=BASE_SEED + 77_000 + n_layers, outlier_frac=0.05)
+
 CALIB_DRAW = 1_000_001     # draw_seed of the calibration draw
 TEST_DRAW = 1_000_002      # draw_seed of the evaluation draw
