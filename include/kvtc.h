@@ -249,6 +249,44 @@ kvtc_status kvtc_decode_batch_blocked(const kvtc_batch* batch, const kvtc_job* j
                                       uint32_t* status_dev, kvtc_stream stream);
 
 /*
+ * ---- Plans over the concatenated features of several layers --------------------------------
+ * (paper, Section "Feature decorrelation": the keys or values of l layers and h heads are concatenated
+ * into p = l * h * d_head features under ONE basis; appendix "PCA matrix sizes": that basis is cut to its
+ * first 8K or 10K components before the bit allocation removes more; appendix "PCA feature concat size
+ * vs performance".)  Such a plan keeps thousands of coordinates, more than one record of the coder holds,
+ * so its byte layout (on which the paper is silent) is cut into SECTIONS: consecutive kept groups are
+ * gathered greedily into sections of at most 1024 coordinates and 64 groups; section c is coded exactly
+ * as a plan made of its groups alone, and the stream of a tensor of T tokens is the T records of section
+ * 0, then the T records of section 1, ..., each section starting on a 16-byte boundary of the stream.
+ * The headers and codes are those of the unsectioned method (a group's quantisation never looks outside
+ * the group); decoding sums the sections' products in fp32 and adds the mean once.
+ *   kvtc_wide_create  arguments as kvtc_plan_create, with r and n_groups unbounded and every group of at
+ *                     most 1024 coordinates (a multiple of 16).  Host arrays may be freed on return.
+ *   kvtc_wide_encode  x_dev and layout as kvtc_encode_blocked (per-layer tensors [layers][tokens][1024]
+ *                     are read in place: no concatenated copy); out_dev 16-byte aligned, out_cap >=
+ *                     kvtc_wide_encoded_bytes(w, n_tokens) else KVTC_E_SMALL.  One launch per section.
+ *   kvtc_wide_decode  x_out_dev and layout as kvtc_decode_blocked.  For bf16 output the caller passes
+ *                     sum_dev, an fp32 workspace [n_tokens][p] (16-byte aligned) in which the sections are
+ *                     summed before ONE rounding to bf16; for fp32 output they are summed in x_out_dev
+ *                     itself and sum_dev is ignored (may be null).  Sections after the first add with
+ *                     hardware float adds in memory; the launches are ordered on the stream, so every
+ *                     element receives its terms in section order and results are reproducible.
+ * Neither call allocates or synchronises.
+ */
+typedef struct kvtc_wide kvtc_wide;
+kvtc_status kvtc_wide_create(kvtc_wide** out, int p, int r, const float* mu_host, const uint16_t* v_kept_bf16_host,
+                             int n_groups, const kvtc_group* groups_host, kvtc_stream stream);
+void kvtc_wide_destroy(kvtc_wide* w);
+int kvtc_wide_sections(const kvtc_wide* w);
+size_t kvtc_wide_section_record_bytes(const kvtc_wide* w, int section);      /* 0 outside 0..sections-1 */
+size_t kvtc_wide_record_bytes(const kvtc_wide* w);                            /* bytes per token over all sections */
+size_t kvtc_wide_encoded_bytes(const kvtc_wide* w, int64_t n_tokens);         /* stream length, alignment gaps included */
+kvtc_status kvtc_wide_encode(const kvtc_wide* w, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens,
+                             const kvtc_layout* layout, void* out_dev, size_t out_cap, kvtc_stream stream);
+kvtc_status kvtc_wide_decode(const kvtc_wide* w, const void* in_dev, size_t in_bytes, int64_t n_tokens, void* x_out_dev,
+                             kvtc_dtype dtype, const kvtc_layout* layout, float* sum_dev, kvtc_stream stream);
+
+/*
  * ---- Positional rotation of keys ----------------------------------------------------------
  * (paper, Section "Feature decorrelation": the rotary positional embedding is removed from keys
  * before they are transform-coded, because it hides their low-rank structure, and decoded keys are

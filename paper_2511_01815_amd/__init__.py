@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     kvtc_window_split, kvtc_cr_with_window, kvtc_fp8_pack, kvtc_fp8_unpack, kvtc_offsets_append,
     kvtc_probe_stream, kvtc_probe_mfma_bf16, PROBE_READ, PROBE_WRITE, PROBE_COPY,
     kvtc_rope, ROPE_HALF, ROPE_INTERLEAVED,
+    WidePlan, kvtc_wide_create, kvtc_wide_destroy, kvtc_wide_sections, kvtc_wide_section_record_bytes, kvtc_wide_record_bytes,
+    kvtc_wide_encoded_bytes, kvtc_wide_encode, kvtc_wide_decode,
     KvtcLayout, layout, kvtc_encode_blocked, kvtc_decode_blocked, kvtc_encode_batch_blocked, kvtc_decode_batch_blocked,
 )
 from . import bundles  # noqa: F401

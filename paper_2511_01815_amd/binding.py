@@ -85,6 +85,21 @@ def lib() -> C.CDLL:
         L.kvtc_decode_batch_blocked.argtypes = [vp, vp, C.c_int, vp, sz, vp, vp, C.c_int, lp, vp, vp]
         for f in (L.kvtc_encode_blocked, L.kvtc_decode_blocked, L.kvtc_encode_batch_blocked, L.kvtc_decode_batch_blocked):
             f.restype = C.c_int
+        L.kvtc_wide_create.argtypes = [C.POINTER(vp), C.c_int, C.c_int, vp, vp, C.c_int, vp, vp]
+        L.kvtc_wide_destroy.argtypes = [vp]
+        L.kvtc_wide_destroy.restype = None
+        L.kvtc_wide_sections.argtypes = [vp]
+        L.kvtc_wide_sections.restype = C.c_int
+        L.kvtc_wide_section_record_bytes.argtypes = [vp, C.c_int]
+        L.kvtc_wide_section_record_bytes.restype = sz
+        L.kvtc_wide_record_bytes.argtypes = [vp]
+        L.kvtc_wide_record_bytes.restype = sz
+        L.kvtc_wide_encoded_bytes.argtypes = [vp, i64]
+        L.kvtc_wide_encoded_bytes.restype = sz
+        L.kvtc_wide_encode.argtypes = [vp, vp, C.c_int, i64, lp, vp, sz, vp]
+        L.kvtc_wide_decode.argtypes = [vp, vp, sz, i64, vp, C.c_int, lp, vp, vp]
+        for f in (L.kvtc_wide_create, L.kvtc_wide_encode, L.kvtc_wide_decode):
+            f.restype = C.c_int
         L.kvtc_rope.argtypes = [vp, C.c_int, i64, C.c_int, C.c_int, i64, i64, vp, i64, C.c_double, C.c_int, C.c_int, vp]
         L.kvtc_rope.restype = C.c_int
         L.kvtc_last_error.argtypes = []
@@ -292,6 +307,68 @@ class Plan:
     def close(self):
         if getattr(self, "handle", None):
             kvtc_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def kvtc_wide_create(p: int, r: int, mu_host: np.ndarray, v_kept_host: np.ndarray,
+                     groups: Sequence[Sequence[int]], stream=None) -> int:
+    mu = np.ascontiguousarray(mu_host, dtype=np.float32)
+    v = np.ascontiguousarray(v_kept_host, dtype=np.uint16)
+    assert mu.shape == (p,) and v.shape == (p, r), (mu.shape, v.shape)
+    arr = (_Group * len(groups))(*[_Group(int(n), int(b), 0) for n, b in groups])
+    out = C.c_void_p()
+    _check(lib().kvtc_wide_create(C.byref(out), p, r, mu.ctypes.data, v.ctypes.data, len(groups),
+                                  C.cast(arr, C.c_void_p), _stream(stream)))
+    return out.value
+
+
+def kvtc_wide_destroy(w: int) -> None:
+    lib().kvtc_wide_destroy(w)
+
+
+def kvtc_wide_sections(w: int) -> int:
+    return lib().kvtc_wide_sections(w)
+
+
+def kvtc_wide_section_record_bytes(w: int, section: int) -> int:
+    return lib().kvtc_wide_section_record_bytes(w, section)
+
+
+def kvtc_wide_record_bytes(w: int) -> int:
+    return lib().kvtc_wide_record_bytes(w)
+
+
+def kvtc_wide_encoded_bytes(w: int, n_tokens: int) -> int:
+    return lib().kvtc_wide_encoded_bytes(w, n_tokens)
+
+
+def kvtc_wide_encode(w, x_dev, dtype: int, n_tokens: int, lay, out_dev, out_cap: int, stream=None) -> None:
+    _check(lib().kvtc_wide_encode(w, _ptr(x_dev), dtype, n_tokens, C.byref(lay), _ptr(out_dev), out_cap, _stream(stream)))
+
+
+def kvtc_wide_decode(w, in_dev, in_bytes: int, n_tokens: int, x_out_dev, dtype: int, lay, sum_dev=None, stream=None) -> None:
+    _check(lib().kvtc_wide_decode(w, _ptr(in_dev), in_bytes, n_tokens, _ptr(x_out_dev), dtype, C.byref(lay),
+                                  _ptr(sum_dev) if sum_dev is not None else None, _stream(stream)))
+
+
+class WidePlan:
+    """Owns a kvtc_wide handle."""
+
+    def __init__(self, p: int, r: int, mu_host, v_kept_host, groups, stream=None):
+        self.p, self.r = p, r
+        self.handle = kvtc_wide_create(p, r, mu_host, v_kept_host, groups, stream)
+        self.record_bytes = kvtc_wide_record_bytes(self.handle)
+        self.n_sections = kvtc_wide_sections(self.handle)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            kvtc_wide_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

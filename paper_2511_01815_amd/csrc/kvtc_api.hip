@@ -3,6 +3,7 @@
 // and the on-device prefix sum of stream offsets.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -219,8 +220,18 @@ uint32_t kvtc_host_code(float d, uint16_t shift16, uint16_t scale16, int bits) {
     return (uint32_t)code_of(d, f16_bits_to_f32(shift16), inv, (float)((1u << bits) - 1u));
 }
 
+// v_kept_host: [p] rows of ldv elements, of which the first r are the plan's columns.  dec_zero_mu: the decode side adds
+// no mean (a further section of a sectioned plan: the first section's decode has added it already).
+static kvtc_status plan_create_impl(kvtc_plan** out, int p, int r, const float* mu_host, const uint16_t* v_kept_host, size_t ldv,
+                                    int n_groups, const kvtc_group* groups_host, bool dec_zero_mu, kvtc_stream stream);
+
 kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host, const uint16_t* v_kept_host,
                              int n_groups, const kvtc_group* groups_host, kvtc_stream stream) {
+    return plan_create_impl(out, p, r, mu_host, v_kept_host, (size_t)(r > 0 ? r : 0), n_groups, groups_host, false, stream);
+}
+
+static kvtc_status plan_create_impl(kvtc_plan** out, int p, int r, const float* mu_host, const uint16_t* v_kept_host, size_t ldv,
+                                    int n_groups, const kvtc_group* groups_host, bool dec_zero_mu, kvtc_stream stream) {
     if (out) *out = nullptr;
     if (!out || !mu_host || !v_kept_host || !groups_host) return fail(KVTC_E_ARG, "kvtc_plan_create: null argument");
     if (p <= 0 || p % 64 != 0) return fail(KVTC_E_ARG, "kvtc_plan_create: p=%d must be a positive multiple of 64", p);
@@ -330,7 +341,7 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
                 if (j >= r) continue;
                 uint16_t* dst = &venc[(((size_t)ks * ntp + ct) * 64 + lane) * 8];
                 const int f0 = 16 * ks + 8 * (lane >> 5);
-                for (int e = 0; e < 8; ++e) dst[e] = v_kept_host[(size_t)(f0 + e) * r + j];
+                for (int e = 0; e < 8; ++e) dst[e] = v_kept_host[(size_t)(f0 + e) * ldv + j];
             }
     for (int ft = 0; ft < p / 32; ++ft)
         for (int ks = 0; ks < 2 * d.dec_nct; ++ks)
@@ -340,16 +351,16 @@ kvtc_status kvtc_plan_create(kvtc_plan** out, int p, int r, const float* mu_host
                 const int j0 = 32 * (ks >> 1) + 16 * (lane >> 5) + 8 * (ks & 1);
                 uint16_t* dst = &vdec[(((size_t)ft * stage_u4) + (size_t)ks * 64 + lane) * 8];
                 for (int e = 0; e < 8; ++e)
-                    if (j0 + e < r) dst[e] = v_kept_host[(size_t)f * r + j0 + e];
+                    if (j0 + e < r) dst[e] = v_kept_host[(size_t)f * ldv + j0 + e];
             }
     for (int ft = 0; ft < p / 32; ++ft) {
         float m[32];
-        for (int l = 0; l < 32; ++l) m[l] = mu_host[64 * (ft >> 1) + 2 * l + (ft & 1)];      // the lane order of the tile
+        for (int l = 0; l < 32; ++l) m[l] = dec_zero_mu ? 0.0f : mu_host[64 * (ft >> 1) + 2 * l + (ft & 1)];      // the lane order of the tile
         memcpy(&vdec[((size_t)ft * stage_u4 + (size_t)2 * d.dec_nct * 64) * 8], m, sizeof(m));
     }
     for (int j = 0; j < r; ++j) {
         double c = 0.0;
-        for (int f = 0; f < p; ++f) c += (double)mu_host[f] * (double)bf16_bits_to_float(v_kept_host[(size_t)f * r + j]);
+        for (int f = 0; f < p; ++f) c += (double)mu_host[f] * (double)bf16_bits_to_float(v_kept_host[(size_t)f * ldv + j]);
         negc[j] = -(float)c;
     }
     {
@@ -479,7 +490,7 @@ static kvtc_status check_layout(const char* who, const void* x, kvtc_dtype dtype
 static kvtc_status encode_single(const char* who, const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens,
                                  const kvtc_layout* layout, void* out_dev, size_t out_cap, kvtc_stream stream);
 static kvtc_status decode_single(const char* who, const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens,
-                                 void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream);
+                                 void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream, bool accumulate = false);
 
 kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int64_t ld_x,
                         void* out_dev, size_t out_cap, kvtc_stream stream) {
@@ -545,7 +556,8 @@ static kvtc_status encode_single(const char* who, const kvtc_plan* plan, const v
 }
 
 static kvtc_status decode_single(const char* who, const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens,
-                                 void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream) {
+                                 void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream, bool accumulate) {
+    if (accumulate && dtype != KVTC_F32) return fail(KVTC_E_ARG, "%s: sections are summed in fp32 only", who);
     if (!plan) return fail(KVTC_E_ARG, "kvtc_decode: null plan");
     if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_decode: n_tokens=%lld", (long long)n_tokens);
     if (n_tokens == 0) return KVTC_OK;
@@ -568,6 +580,7 @@ static kvtc_status decode_single(const char* who, const kvtc_plan* plan, const v
     a.x_blk_jump = xl.blk_jump;
     a.stream_buf = const_cast<void*>(in_dev);
     a.cap = in_bytes;
+    a.dec_accumulate = accumulate ? 1 : 0;
     const int slots = cu_count() * plan->h.dec_wgs;
     // A tensor short enough for all its 128-token tiles to run at once takes the variant with one token
     // tile per wave (same plan data: it depends on the padded width only).
@@ -954,6 +967,166 @@ kvtc_status kvtc_decode_batch_blocked(const kvtc_batch* batch, const kvtc_job* j
         a.dec_ring_off = lay.ring_off;
         hipError_t e = launch_decode(a, dtype, v.key, cu_count() * v.wgs, lay.lds_bytes, static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_decode_batch: launch failed: %s", hipGetErrorString(e));
+    }
+    return KVTC_OK;
+}
+
+}  // extern "C"
+
+// ---- sectioned plans: more kept coordinates than one record holds ---------------------------------
+struct kvtc_wide {
+    int p, r;
+    std::vector<kvtc_plan*> sections;
+    size_t record_bytes;            // over all sections
+};
+
+namespace {
+
+constexpr int kSectionCoords = 1024, kSectionGroups = 64;
+
+// fp32 rows [n_tokens][p] (contiguous) -> bf16 at the caller's layout, rounding to nearest even; 8 features per thread
+__global__ void __launch_bounds__(256) round_to_bf16_kernel(const float* src, uint16_t* dst, int64_t n_tokens, int p, int64_t token_stride,
+                                                           int blk_log2, int64_t blk_jump) {
+    const int per_row = p / 8;
+    const int64_t total = n_tokens * per_row;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t t = i / per_row;
+        const int f = (int)(i - t * per_row) * 8;
+        const float4 a = *reinterpret_cast<const float4*>(src + t * p + f);
+        const float4 b = *reinterpret_cast<const float4*>(src + t * p + f + 4);
+        typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+        bf16x8 v;
+        v[0] = (__bf16)a.x; v[1] = (__bf16)a.y; v[2] = (__bf16)a.z; v[3] = (__bf16)a.w;
+        v[4] = (__bf16)b.x; v[5] = (__bf16)b.y; v[6] = (__bf16)b.z; v[7] = (__bf16)b.w;
+        const int64_t off = t * token_stride + f + (blk_log2 ? (int64_t)(f >> blk_log2) * blk_jump : 0);
+        *reinterpret_cast<uint4*>(dst + off) = __builtin_bit_cast(uint4, v);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+kvtc_status kvtc_wide_create(kvtc_wide** out, int p, int r, const float* mu_host, const uint16_t* v_kept_host, int n_groups,
+                             const kvtc_group* groups_host, kvtc_stream stream) {
+    if (out) *out = nullptr;
+    if (!out || !mu_host || !v_kept_host || !groups_host) return fail(KVTC_E_ARG, "kvtc_wide_create: null argument");
+    if (p <= 0 || p % 64 != 0) return fail(KVTC_E_ARG, "kvtc_wide_create: p=%d must be a positive multiple of 64", p);
+    if (n_groups < 1 || r < 16) return fail(KVTC_E_ARG, "kvtc_wide_create: r=%d, n_groups=%d", r, n_groups);
+    long sum = 0;
+    for (int g = 0; g < n_groups; ++g) {
+        if (groups_host[g].n < 1 || groups_host[g].n > kSectionCoords)
+            return fail(KVTC_E_ARG, "kvtc_wide_create: group %d has %d coordinates (1..%d allowed)", g, (int)groups_host[g].n, kSectionCoords);
+        sum += groups_host[g].n;
+    }
+    if (sum != r) return fail(KVTC_E_ARG, "kvtc_wide_create: group sizes sum to %ld, r=%d", sum, r);
+    kvtc_wide* w = new (std::nothrow) kvtc_wide;
+    if (!w) return fail(KVTC_E_NOMEM, "kvtc_wide_create: host allocation failed");
+    w->p = p;
+    w->r = r;
+    w->record_bytes = 0;
+    // consecutive groups -> sections, greedily: a section takes groups while it stays within 1024 coordinates and 64 groups
+    int g0 = 0, j0 = 0;
+    while (g0 < n_groups) {
+        int g1 = g0, n = 0;
+        while (g1 < n_groups && g1 - g0 < kSectionGroups && n + groups_host[g1].n <= kSectionCoords) n += groups_host[g1++].n;
+        kvtc_plan* sec = nullptr;
+        kvtc_status st = plan_create_impl(&sec, p, n, mu_host, v_kept_host + j0, (size_t)r, g1 - g0, groups_host + g0,
+                                          /*dec_zero_mu=*/g0 != 0, stream);
+        if (st == KVTC_OK) {
+            try { w->sections.push_back(sec); } catch (const std::bad_alloc&) { kvtc_plan_destroy(sec); st = fail(KVTC_E_NOMEM, "kvtc_wide_create: host allocation failed"); }
+        }
+        if (st != KVTC_OK) {
+            kvtc_wide_destroy(w);
+            return st;
+        }
+        w->record_bytes += sec->record_bytes;
+        g0 = g1;
+        j0 += n;
+    }
+    *out = w;
+    return KVTC_OK;
+}
+
+void kvtc_wide_destroy(kvtc_wide* w) {
+    if (!w) return;
+    for (kvtc_plan* s : w->sections) kvtc_plan_destroy(s);
+    delete w;
+}
+
+int kvtc_wide_sections(const kvtc_wide* w) { return w ? (int)w->sections.size() : 0; }
+
+size_t kvtc_wide_section_record_bytes(const kvtc_wide* w, int section) {
+    return (w && section >= 0 && section < (int)w->sections.size()) ? w->sections[section]->record_bytes : 0;
+}
+
+size_t kvtc_wide_record_bytes(const kvtc_wide* w) { return w ? w->record_bytes : 0; }
+
+size_t kvtc_wide_encoded_bytes(const kvtc_wide* w, int64_t n_tokens) {
+    if (!w || n_tokens <= 0) return 0;
+    size_t pos = 0;
+    for (const kvtc_plan* s : w->sections) pos = align_up(pos, 16) + s->record_bytes * (size_t)n_tokens;
+    return pos;
+}
+
+kvtc_status kvtc_wide_encode(const kvtc_wide* w, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens, const kvtc_layout* layout,
+                             void* out_dev, size_t out_cap, kvtc_stream stream) {
+    if (!w) return fail(KVTC_E_ARG, "kvtc_wide_encode: null plan");
+    if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_wide_encode: n_tokens=%lld", (long long)n_tokens);
+    if (n_tokens == 0) return KVTC_OK;
+    if (!out_dev) return fail(KVTC_E_ARG, "kvtc_wide_encode: null buffer");
+    if (out_cap < kvtc_wide_encoded_bytes(w, n_tokens))
+        return fail(KVTC_E_SMALL, "kvtc_wide_encode: out_cap=%zu < %zu", out_cap, kvtc_wide_encoded_bytes(w, n_tokens));
+    size_t pos = 0;
+    for (const kvtc_plan* s : w->sections) {          // a launch per section, each over all tokens
+        pos = align_up(pos, 16);
+        const size_t bytes = s->record_bytes * (size_t)n_tokens;
+        kvtc_status st = encode_single("kvtc_wide_encode", s, x_dev, dtype, n_tokens, layout, static_cast<char*>(out_dev) + pos, bytes, stream);
+        if (st != KVTC_OK) return st;
+        pos += bytes;
+    }
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_wide_decode(const kvtc_wide* w, const void* in_dev, size_t in_bytes, int64_t n_tokens, void* x_out_dev, kvtc_dtype dtype,
+                             const kvtc_layout* layout, float* sum_dev, kvtc_stream stream) {
+    if (!w) return fail(KVTC_E_ARG, "kvtc_wide_decode: null plan");
+    if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_wide_decode: n_tokens=%lld", (long long)n_tokens);
+    if (n_tokens == 0) return KVTC_OK;
+    if (!in_dev || !x_out_dev) return fail(KVTC_E_ARG, "kvtc_wide_decode: null buffer");
+    if (!dtype_ok(dtype)) return fail(KVTC_E_ARG, "kvtc_wide_decode: unknown dtype %d", (int)dtype);
+    if (in_bytes < kvtc_wide_encoded_bytes(w, n_tokens))
+        return fail(KVTC_E_SMALL, "kvtc_wide_decode: in_bytes=%zu < %zu", in_bytes, kvtc_wide_encoded_bytes(w, n_tokens));
+    // the sections' products are summed in fp32: straight in the output when that is fp32, else in the caller's workspace
+    XLayout xl;
+    kvtc_status st = check_layout("kvtc_wide_decode", x_out_dev, dtype, layout, w->p, n_tokens, &xl);
+    if (st != KVTC_OK) return st;
+    const kvtc_layout flat = {w->p, 0, 0, 0};
+    void* target = x_out_dev;
+    const kvtc_layout* tlay = layout;
+    if (dtype == KVTC_BF16) {
+        if (!sum_dev) return fail(KVTC_E_ARG, "kvtc_wide_decode: bf16 output needs the fp32 workspace sum_dev [n_tokens][p]");
+        if (reinterpret_cast<uintptr_t>(sum_dev) & 15u) return fail(KVTC_E_ARG, "kvtc_wide_decode: sum_dev must be 16-byte aligned");
+        target = sum_dev;
+        tlay = &flat;
+    }
+    size_t pos = 0;
+    bool first = true;
+    for (const kvtc_plan* s : w->sections) {
+        pos = align_up(pos, 16);
+        const size_t bytes = s->record_bytes * (size_t)n_tokens;
+        st = decode_single("kvtc_wide_decode", s, static_cast<const char*>(in_dev) + pos, bytes, n_tokens, target, KVTC_F32, tlay, stream, !first);
+        if (st != KVTC_OK) return st;
+        pos += bytes;
+        first = false;
+    }
+    if (dtype == KVTC_BF16) {
+        const int64_t items = n_tokens * (w->p / 8);
+        const int grid = (int)std::min<int64_t>((items + 255) / 256, (int64_t)cu_count() * 8);
+        hipLaunchKernelGGL(round_to_bf16_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream), sum_dev,
+                           static_cast<uint16_t*>(x_out_dev), n_tokens, w->p, xl.ld, xl.blk_log2, xl.blk_jump);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_wide_decode: launch failed: %s", hipGetErrorString(e));
     }
     return KVTC_OK;
 }

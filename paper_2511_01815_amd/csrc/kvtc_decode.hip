@@ -117,7 +117,7 @@ __device__ __forceinline__ int issue_records(const KernelArgs& a, const TileRef&
 // published.  With `prefetch` the ring does not overlap them: the first basis slab is requested
 // before unpacking, and the records of the workgroup's next tile (if any) are requested during
 // the first step of the feature sweep.
-template <int NCT, int TT, typename OT>
+template <int NCT, int TT, typename OT, bool ACC>
 __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr, const KernelArgs& a, uint4* work, uint4* ring,
                                             bool prefetch, bool has_next, const TileRef& next, const PlanDec& Pn) {
     constexpr int TOK_W = 32 * TT;
@@ -267,16 +267,34 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
             // accumulators need)
             uint32_t lrow = lane_row;
             asm volatile("" : "+v"(lrow));
+            if constexpr (ACC) {
+                // a further section of a sectioned plan: its part of the product is ADDED to what the earlier
+                // sections left in the fp32 output (hardware float adds in memory, nothing returned).  Rows past
+                // the tensor's end are skipped, not redirected: adding the last row's values twice would be wrong.
+                static_assert(sizeof(OT) == 4, "sections are summed in fp32");
 #pragma unroll
-            for (int k = 0; k < NST; ++k) {
-                const int tt = k / 16, i = k % 16;
-                const uint32_t row = min(lrow + (uint32_t)(tt * 32 + 8 * (i / 4) + i % 4), last_row);
-                char* dst = ob + (__umul24(row, ldb) + lane_col);              // row < 256, ldb <= 2^23
-                if constexpr (sizeof(OT) == 2) *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(acc0[tt][i], acc1[tt][i]);
-                else *reinterpret_cast<float2*>(dst) = make_float2(acc0[tt][i], acc1[tt][i]);
+                for (int k = 0; k < NST; ++k) {
+                    const int tt = k / 16, i = k % 16;
+                    const uint32_t row = lrow + (uint32_t)(tt * 32 + 8 * (i / 4) + i % 4);
+                    if (row <= last_row) {
+                        float* dst = reinterpret_cast<float*>(ob + (__umul24(row, ldb) + lane_col));
+                        unsafeAtomicAdd(dst, acc0[tt][i]);
+                        unsafeAtomicAdd(dst + 1, acc1[tt][i]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < NST; ++k) {
+                    const int tt = k / 16, i = k % 16;
+                    const uint32_t row = min(lrow + (uint32_t)(tt * 32 + 8 * (i / 4) + i % 4), last_row);
+                    char* dst = ob + (__umul24(row, ldb) + lane_col);              // row < 256, ldb <= 2^23
+                    if constexpr (sizeof(OT) == 2) *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(acc0[tt][i], acc1[tt][i]);
+                    else *reinterpret_cast<float2*>(dst) = make_float2(acc0[tt][i], acc1[tt][i]);
+                }
             }
         }
-        if (more) wait_vmem<NST>(); else wait_vmem<0>();
+        // (the adds are a data-dependent number of operations, so after them the wait is for everything)
+        if (more && !ACC) wait_vmem<NST>(); else wait_vmem<0>();
         __syncthreads();
     }
 }
@@ -296,25 +314,25 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
 template <int TT, int CLS> constexpr int dec_wgs_per_cu() { return CLS <= 4 ? 3 : (CLS <= 10 ? 2 : 1); }
 
 // The widths built for each class; a plan's tile count is rounded up to the next of them at plan creation.
-template <int CLS, int TT, typename OT>
+template <int CLS, int TT, typename OT, bool ACC>
 __device__ __forceinline__ void decode_tile_of_class(const PlanDec& P, const TileRef& tr, const KernelArgs& a, uint4* work, uint4* ring,
                                                      bool prefetch, bool has_next, const TileRef& next, const PlanDec& Pn) {
-#define KVTC_W(N) case N: decode_tile<N, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break;
+#define KVTC_W(N) case N: decode_tile<N, TT, OT, ACC>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break;
     if constexpr (CLS == 4) {
-        switch (P.dec_nct) { KVTC_W(2) default: decode_tile<4, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
+        switch (P.dec_nct) { KVTC_W(2) default: decode_tile<4, TT, OT, ACC>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
     } else if constexpr (CLS == 10) {
-        switch (P.dec_nct) { KVTC_W(6) KVTC_W(7) KVTC_W(8) KVTC_W(9) default: decode_tile<10, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
+        switch (P.dec_nct) { KVTC_W(6) KVTC_W(7) KVTC_W(8) KVTC_W(9) default: decode_tile<10, TT, OT, ACC>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
     } else if constexpr (CLS == 18) {
-        switch (P.dec_nct) { KVTC_W(12) KVTC_W(16) KVTC_W(17) default: decode_tile<18, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
+        switch (P.dec_nct) { KVTC_W(12) KVTC_W(16) KVTC_W(17) default: decode_tile<18, TT, OT, ACC>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
     } else if constexpr (CLS == 24) {
-        switch (P.dec_nct) { KVTC_W(20) default: decode_tile<24, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
+        switch (P.dec_nct) { KVTC_W(20) default: decode_tile<24, TT, OT, ACC>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break; }
     } else {
-        decode_tile<32, TT, OT>(P, tr, a, work, ring, prefetch, has_next, next, Pn);
+        decode_tile<32, TT, OT, ACC>(P, tr, a, work, ring, prefetch, has_next, next, Pn);
     }
 #undef KVTC_W
 }
 
-template <typename OT, int TT, int CLS>
+template <typename OT, int TT, int CLS, bool ACC = false>
 __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, CLS>())) kvtc_decode_kernel(const KernelArgs a) {
     extern __shared__ uint4 smem[];
     uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
@@ -341,7 +359,7 @@ __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, CLS>())) kvtc_de
             Pn = load_plan_dec(a.plans + trn.plan);
             Pn.dec_tok_wg = 4 * 32 * TT;
         }
-        decode_tile_of_class<CLS, TT, OT>(P, tr, a, work, ring, prefetch, has_next && prefetch, trn, Pn);
+        decode_tile_of_class<CLS, TT, OT, ACC>(P, tr, a, work, ring, prefetch, has_next && prefetch, trn, Pn);
         if (!has_next) break;
         tile = next;
         tr = trn;
@@ -366,6 +384,7 @@ hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int key, int gri
 #define KVTC_X(TT, CLS)                                                                                        \
     case (TT) * 100 + (CLS):                                                                                   \
         fn = dtype == KVTC_BF16 ? reinterpret_cast<const void*>(&kvtc_decode_kernel<uint16_t, TT, CLS>)        \
+             : a.dec_accumulate ? reinterpret_cast<const void*>(&kvtc_decode_kernel<float, TT, CLS, true>)     \
                                 : reinterpret_cast<const void*>(&kvtc_decode_kernel<float, TT, CLS>);          \
         break;
         KVTC_DEC_VARIANTS(KVTC_X)

@@ -74,6 +74,7 @@ struct KernelArgs {
     int32_t enc_short;         // encode: this launch runs the short-job variants (jobs of at most enc_short_max tokens whose plan has one) ...
     int32_t enc_short_max;     // ... and the launches of the bulk variants leave those jobs alone; 0 = no job counts as short
     int32_t dec_short;         // decode: this launch runs the one-token-tile-per-wave variant of every plan (128-token tiles)
+    int32_t dec_accumulate;    // decode, fp32 output only: add the product to the output instead of storing it (further sections of a sectioned plan)
 };
 
 struct TileRef {
