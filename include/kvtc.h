@@ -287,6 +287,42 @@ kvtc_status kvtc_wide_decode(const kvtc_wide* w, const void* in_dev, size_t in_b
                              kvtc_dtype dtype, const kvtc_layout* layout, float* sum_dev, kvtc_stream stream);
 
 /*
+ * ---- Lossless stage over the packed records --------------------------------------------------
+ * (paper, Section "Entropy coding": the quantiser's byte array is passed through a lossless coder on the
+ * GPU -- a general-purpose DEFLATE in the paper's implementation; appendix "Ablations of lossless
+ * compression".)  This library runs a byte-wise entropy coder matched to the records' fixed layout: a
+ * static prefix code PER BYTE POSITION of the record (byte k of every record -- the high byte of a group's
+ * shift, the third byte of the 4-bit codes -- has a distribution of its own).  The tables are data from
+ * calibration: 256 code lengths (1..12, satisfying Kraft's inequality) per position; codes are canonical
+ * (by length, then by symbol) and written most significant code bit first into a bit string that fills
+ * bytes from their least significant bit.  Container of a tensor's n_tokens records, little-endian:
+ *     uint32 chunk_off[n_chunks + 1]   byte offset of each 64-token chunk's bit string in the payload; last: payload length
+ *     uint16 len_bits[64 * n_chunks]   bits of each token's code string (0 beyond the last token)
+ *     payload                          the chunks' bit strings, each zero-padded to a multiple of 4 bytes; inside a
+ *                                      chunk the tokens' strings follow each other bit by bit
+ *   kvtc_entropy_create   code_len_host [record_bytes][256]; record_bytes a multiple of 4, at most 576
+ *                         (KVTC_E_UNSUPPORTED beyond).  The array may be freed on return.
+ *   kvtc_entropy_bound    bytes the container of n_tokens records can reach at most.
+ *   kvtc_entropy_encode   records_dev: n_tokens records back to back (4-byte aligned).  out_dev 4-byte aligned;
+ *                         out_cap must hold at least the directory (else KVTC_E_SMALL); with out_cap >=
+ *                         kvtc_entropy_bound nothing can be cut short, otherwise chunks that would end beyond
+ *                         out_cap are left unwritten.  *out_bytes_dev (device, 8-byte aligned) receives the
+ *                         container's length -- compare it with out_cap after synchronising.  Three launches.
+ *   kvtc_entropy_decode   in_dev/in_bytes: a container; records_out_dev: n_tokens * record_bytes bytes
+ *                         (out_cap smaller: KVTC_E_SMALL).  Reads are clamped to in_bytes: a damaged container
+ *                         gives wrong bytes, never a fault.
+ * Neither call allocates or synchronises.
+ */
+typedef struct kvtc_entropy kvtc_entropy;
+kvtc_status kvtc_entropy_create(kvtc_entropy** out, int record_bytes, const uint8_t* code_len_host, kvtc_stream stream);
+void kvtc_entropy_destroy(kvtc_entropy* e);
+size_t kvtc_entropy_bound(const kvtc_entropy* e, int64_t n_tokens);
+kvtc_status kvtc_entropy_encode(const kvtc_entropy* e, const void* records_dev, int64_t n_tokens, void* out_dev, size_t out_cap,
+                                uint64_t* out_bytes_dev, kvtc_stream stream);
+kvtc_status kvtc_entropy_decode(const kvtc_entropy* e, const void* in_dev, size_t in_bytes, int64_t n_tokens,
+                                void* records_out_dev, size_t out_cap, kvtc_stream stream);
+
+/*
  * ---- Positional rotation of keys ----------------------------------------------------------
  * (paper, Section "Feature decorrelation": the rotary positional embedding is removed from keys
  * before they are transform-coded, because it hides their low-rank structure, and decoded keys are

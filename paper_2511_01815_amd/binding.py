@@ -100,6 +100,15 @@ def lib() -> C.CDLL:
         L.kvtc_wide_decode.argtypes = [vp, vp, sz, i64, vp, C.c_int, lp, vp, vp]
         for f in (L.kvtc_wide_create, L.kvtc_wide_encode, L.kvtc_wide_decode):
             f.restype = C.c_int
+        L.kvtc_entropy_create.argtypes = [C.POINTER(vp), C.c_int, vp, vp]
+        L.kvtc_entropy_destroy.argtypes = [vp]
+        L.kvtc_entropy_destroy.restype = None
+        L.kvtc_entropy_bound.argtypes = [vp, i64]
+        L.kvtc_entropy_bound.restype = sz
+        L.kvtc_entropy_encode.argtypes = [vp, vp, i64, vp, sz, vp, vp]
+        L.kvtc_entropy_decode.argtypes = [vp, vp, sz, i64, vp, sz, vp]
+        for f in (L.kvtc_entropy_create, L.kvtc_entropy_encode, L.kvtc_entropy_decode):
+            f.restype = C.c_int
         L.kvtc_rope.argtypes = [vp, C.c_int, i64, C.c_int, C.c_int, i64, i64, vp, i64, C.c_double, C.c_int, C.c_int, vp]
         L.kvtc_rope.restype = C.c_int
         L.kvtc_last_error.argtypes = []
@@ -369,6 +378,49 @@ class WidePlan:
     def close(self):
         if getattr(self, "handle", None):
             kvtc_wide_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def kvtc_entropy_create(record_bytes: int, code_len_host: np.ndarray, stream=None) -> int:
+    L = np.ascontiguousarray(code_len_host, dtype=np.uint8)
+    assert L.shape == (record_bytes, 256), L.shape
+    out = C.c_void_p()
+    _check(lib().kvtc_entropy_create(C.byref(out), record_bytes, L.ctypes.data, _stream(stream)))
+    return out.value
+
+
+def kvtc_entropy_destroy(e: int) -> None:
+    lib().kvtc_entropy_destroy(e)
+
+
+def kvtc_entropy_bound(e: int, n_tokens: int) -> int:
+    return lib().kvtc_entropy_bound(e, n_tokens)
+
+
+def kvtc_entropy_encode(e, records_dev, n_tokens: int, out_dev, out_cap: int, out_bytes_dev, stream=None) -> None:
+    _check(lib().kvtc_entropy_encode(e, _ptr(records_dev), n_tokens, _ptr(out_dev), out_cap, _ptr(out_bytes_dev), _stream(stream)))
+
+
+def kvtc_entropy_decode(e, in_dev, in_bytes: int, n_tokens: int, records_out_dev, out_cap: int, stream=None) -> None:
+    _check(lib().kvtc_entropy_decode(e, _ptr(in_dev), in_bytes, n_tokens, _ptr(records_out_dev), out_cap, _stream(stream)))
+
+
+class EntropyTables:
+    """Owns a kvtc_entropy handle."""
+
+    def __init__(self, record_bytes: int, code_len_host, stream=None):
+        self.record_bytes = record_bytes
+        self.handle = kvtc_entropy_create(record_bytes, code_len_host, stream)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            kvtc_entropy_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

@@ -203,6 +203,17 @@ DecLayout decode_layout(int rec_b, int ring_b, int wgs_per_cu) {
 
 }  // namespace
 
+namespace kvtc {
+// for the library's other sources: records the message kvtc_last_error returns on this thread
+kvtc_status set_error(kvtc_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+}  // namespace kvtc
+
 extern "C" {
 
 const char* kvtc_last_error(void) { return g_err; }
