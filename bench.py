@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 
 
-def cpu_baseline(bundles, x_host, p):
+def cpu_baseline(bundles, x_host, p, entropy_tab=None):
     """The oracle's encode + decode, timed as it stands on this machine's host cores, without and with the
     DEFLATE stage (zlib level 6 over each tensor's stream), and the compression ratios it reports."""
     sys.path.insert(0, os.path.join(ROOT, "oracle"))
@@ -69,7 +69,21 @@ def cpu_baseline(bundles, x_host, p):
             best[k] = min(best[k], t[k])
     plain = best["enc"] + best["dec"]
     with_z = plain + best["defl"] + best["infl"]
-    return dict(value=2 * raw / plain / 1e9, unit="GB/s", cores=threads, kind="oracle",
+    position_code = None
+    if entropy_tab is not None:
+        # the oracle of the GPU's lossless stage (pure Python, bit by bit) on a small part of the first tensor
+        import kvtc_entropy as ke
+        nt = min(1024, x_host[0].shape[0])
+        rec = ko.encode(plans[0], x_host[0][:nt])
+        t0 = time.perf_counter()
+        blob = ke.encode(rec, entropy_tab)
+        t1 = time.perf_counter()
+        ok = bool((ke.decode(blob, nt, rec.shape[1], entropy_tab) == rec).all())
+        t2 = time.perf_counter()
+        position_code = dict(ratio=rec.size / len(blob), encode_MBps_of_stream=rec.size / (t1 - t0) / 1e6,
+                             decode_MBps_of_stream=rec.size / (t2 - t1) / 1e6, round_trip_exact=ok,
+                             what=f"per-position prefix code, oracle in pure Python, first {nt} tokens of the first tensor")
+    return dict(position_code=position_code, value=2 * raw / plain / 1e9, unit="GB/s", cores=threads, kind="oracle",
                 sample=f"{len(plans)} tensors (layer 0, K and V), {x_host[0].shape[0]} tokens each ({raw / 2**20:.0f} MiB raw bf16), "
                        f"encode {raw / best['enc'] / 1e9:.3f} GB/s, decode {raw / best['dec'] / 1e9:.3f} GB/s, best of 2, no DEFLATE",
                 with_deflate=dict(value=2 * raw / with_z / 1e9, unit="GB/s",
@@ -144,6 +158,46 @@ def ceilings(kv, src, dst, reps=7):
     return out
 
 
+def lossless_stage(kv, tables, stream_buf, T, R, dev, reps=5):
+    """The lossless stage over the step's 64 record streams (paper, Section "Entropy coding"): a table set per tensor, all
+    tensors in one kvtc_entropy_encode_batch (three launches) and one kvtc_entropy_decode_batch (one launch); GPU time
+    between HIP events, medians; the decoded records must equal the stream bit for bit."""
+    import numpy as np
+    import torch
+    n = len(tables)
+    tab = kv.EntropyTables(R, tables)
+    bound = (kv.kvtc_entropy_bound(tab.handle, T) + 255) // 256 * 256
+    coded = torch.empty(n * bound, dtype=torch.uint8, device=dev)
+    sizes = torch.zeros(n, dtype=torch.int64, device=dev)
+    back = torch.empty_like(stream_buf)
+    jobs = kv.make_entropy_jobs(list(range(n)), [T] * n, [j * T * R for j in range(n)], [j * bound for j in range(n)], [bound] * n)
+    jobs_dev = torch.from_numpy(jobs.view(np.uint8)).to(dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4 * (reps + 1))]
+    for i in range(reps + 1):
+        ev[4 * i].record()
+        kv.kvtc_entropy_encode_batch(tab.handle, jobs_dev, n, T, stream_buf, stream_buf.numel(), coded, coded.numel(), sizes)
+        ev[4 * i + 1].record()
+        if i == 0:
+            torch.cuda.synchronize()
+            nbytes = sizes.cpu().tolist()
+            assert max(nbytes) <= bound
+            jobs_d = kv.make_entropy_jobs(list(range(n)), [T] * n, [j * T * R for j in range(n)], [j * bound for j in range(n)], nbytes)
+            jobs_d_dev = torch.from_numpy(jobs_d.view(np.uint8)).to(dev)
+        ev[4 * i + 2].record()
+        kv.kvtc_entropy_decode_batch(tab.handle, jobs_d_dev, n, T, coded, coded.numel(), back, back.numel())
+        ev[4 * i + 3].record()
+    torch.cuda.synchronize()
+    assert torch.equal(back, stream_buf), "the lossless stage did not return the stream"
+    enc = statistics.median(ev[4 * i].elapsed_time(ev[4 * i + 1]) for i in range(1, reps + 1))
+    dec = statistics.median(ev[4 * i + 2].elapsed_time(ev[4 * i + 3]) for i in range(1, reps + 1))
+    total, stream_bytes = sum(nbytes), n * T * R
+    tab.close()
+    return dict(encode_ms=enc, decode_ms=dec, stream_GBps_encode=stream_bytes / enc / 1e6, stream_GBps_decode=stream_bytes / dec / 1e6,
+                ratio=stream_bytes / total, coded_bytes=total,
+                what=f"static prefix code per byte position of the record, tables from calibration; {n} tensors x {T} records of {R} B in one "
+                     f"batched call per direction (3 + 1 launches); exact round trip checked")
+
+
 def traffic_from_profiles(workload, cr, kernel):
     """HBM bytes per launch of `kernel` as measured offline with rocprofv3 TCC counters: the tracked summary under
     profiles/ carries lines  `bench-traffic: workload=<w> cr=<cr> kernel=<k> bytes_per_launch=<n>`."""
@@ -176,6 +230,7 @@ def main() -> int:
     ap.add_argument("--cpu-tokens", type=int, default=32768, help="tokens per tensor in the CPU-baseline sample")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the probe kernels (keeps a profile of this run to the coder's kernels)")
+    ap.add_argument("--no-lossless", action="store_true", help="skip the lossless stage over the coded stream")
     ap.add_argument("--append", action="store_true",
                     help="also time one incremental step: 16 new tokens appended to each of the batch's caches")
     ap.add_argument("--copy-check", action="store_true",
@@ -333,12 +388,19 @@ def main() -> int:
     if args.append:
         result["append_step"] = append_step_latency(kv, batch, x, T, plan_of_job, R, stream_buf, dev)
     # What plain kernels reach on this machine, next to the published 8 TB/s and 2.5 PFLOP/s the fractions are quoted against.
+    # The lossless stage over the coded stream (not part of `value`: the headline metric is the coder's two kernels).
+    tables = kb.entropy_tables(args.workload, int(args.cr)) if args.workload == "c3" and args.cr != "full" and not args.no_lossless else None
+    if tables is not None and len(set(R)) == 1 and len(tables) >= n_jobs and tables.shape[1] == R[0]:
+        ll = lossless_stage(kv, tables[:n_jobs], stream_buf, T, R[0], dev)
+        ll["cr_total"] = raw_bytes / ll["coded_bytes"]
+        result["lossless"] = ll
     if not args.no_ceilings:
         result["ceilings"] = ceilings(kv, x, x_hat)
     if not args.no_cpu:
         nt = min(args.cpu_tokens, T)
         xs = [ks.bf16_bits_to_f32(x[j * T:j * T + nt].view(torch.int16).cpu().numpy().view(np.uint16)) for j in (0, 1)]
-        result["cpu_baseline"] = cpu_baseline([bundles[plan_of_job[0]], bundles[plan_of_job[1]]], xs, p)
+        result["cpu_baseline"] = cpu_baseline([bundles[plan_of_job[0]], bundles[plan_of_job[1]]], xs, p,
+                                              tables[0] if tables is not None and "lossless" in result else None)
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result))

@@ -300,27 +300,44 @@ kvtc_status kvtc_wide_decode(const kvtc_wide* w, const void* in_dev, size_t in_b
  *     uint16 len_bits[64 * n_chunks]   bits of each token's code string (0 beyond the last token)
  *     payload                          the chunks' bit strings, each zero-padded to a multiple of 4 bytes; inside a
  *                                      chunk the tokens' strings follow each other bit by bit
- *   kvtc_entropy_create   code_len_host [record_bytes][256]; record_bytes a multiple of 4, at most 576
+ *   kvtc_entropy_create   n_tables table sets (one per tensor whose records share this size), code_len_host
+ *                         [n_tables][record_bytes][256]; record_bytes a multiple of 4, at most 576
  *                         (KVTC_E_UNSUPPORTED beyond).  The array may be freed on return.
  *   kvtc_entropy_bound    bytes the container of n_tokens records can reach at most.
- *   kvtc_entropy_encode   records_dev: n_tokens records back to back (4-byte aligned).  out_dev 4-byte aligned;
- *                         out_cap must hold at least the directory (else KVTC_E_SMALL); with out_cap >=
- *                         kvtc_entropy_bound nothing can be cut short, otherwise chunks that would end beyond
- *                         out_cap are left unwritten.  *out_bytes_dev (device, 8-byte aligned) receives the
- *                         container's length -- compare it with out_cap after synchronising.  Three launches.
+ *   kvtc_entropy_encode   records_dev: n_tokens records back to back (4-byte aligned), coded with table set `table`.
+ *                         out_dev 4-byte aligned; out_cap must hold at least the directory (else KVTC_E_SMALL);
+ *                         with out_cap >= kvtc_entropy_bound nothing can be cut short, otherwise chunks that would
+ *                         end beyond out_cap are left unwritten.  *out_bytes_dev (device, 8-byte aligned) receives
+ *                         the container's length -- compare it with out_cap after synchronising.  Three launches.
  *   kvtc_entropy_decode   in_dev/in_bytes: a container; records_out_dev: n_tokens * record_bytes bytes
  *                         (out_cap smaller: KVTC_E_SMALL).  Reads are clamped to in_bytes: a damaged container
  *                         gives wrong bytes, never a fault.
- * Neither call allocates or synchronises.
+ *   the _batch calls      many tensors in the same launches (three for encode, one for decode).  jobs_dev is a
+ *                         device array (8-byte aligned): table set, token count (at most max_tokens, the host's
+ *                         bound for sizing the launch), the byte offset of the job's records from records_base_dev,
+ *                         of its container from coded_base_dev, and coded_cap = the room for the container
+ *                         (encode) or the container's length (decode); offsets 4-byte aligned.  The host cannot see
+ *                         the table, so a job that is out of range in any way (table, token count, an extent beyond
+ *                         records_bytes / coded_cap, no room for its directory) is left alone by every launch and,
+ *                         in encode, gets coded_bytes_dev[job] = all ones; other jobs get their container's length.
+ *                         At most 65535 jobs per call.
+ * No call allocates or synchronises.
  */
 typedef struct kvtc_entropy kvtc_entropy;
-kvtc_status kvtc_entropy_create(kvtc_entropy** out, int record_bytes, const uint8_t* code_len_host, kvtc_stream stream);
+typedef struct { int32_t table; int32_t n_tokens; uint64_t records_off; uint64_t coded_off; uint64_t coded_cap; } kvtc_entropy_job;
+kvtc_status kvtc_entropy_create(kvtc_entropy** out, int record_bytes, int n_tables, const uint8_t* code_len_host, kvtc_stream stream);
 void kvtc_entropy_destroy(kvtc_entropy* e);
 size_t kvtc_entropy_bound(const kvtc_entropy* e, int64_t n_tokens);
-kvtc_status kvtc_entropy_encode(const kvtc_entropy* e, const void* records_dev, int64_t n_tokens, void* out_dev, size_t out_cap,
-                                uint64_t* out_bytes_dev, kvtc_stream stream);
-kvtc_status kvtc_entropy_decode(const kvtc_entropy* e, const void* in_dev, size_t in_bytes, int64_t n_tokens,
+kvtc_status kvtc_entropy_encode(const kvtc_entropy* e, int table, const void* records_dev, int64_t n_tokens, void* out_dev,
+                                size_t out_cap, uint64_t* out_bytes_dev, kvtc_stream stream);
+kvtc_status kvtc_entropy_decode(const kvtc_entropy* e, int table, const void* in_dev, size_t in_bytes, int64_t n_tokens,
                                 void* records_out_dev, size_t out_cap, kvtc_stream stream);
+kvtc_status kvtc_entropy_encode_batch(const kvtc_entropy* e, const kvtc_entropy_job* jobs_dev, int n_jobs, int64_t max_tokens,
+                                      const void* records_base_dev, size_t records_bytes, void* coded_base_dev, size_t coded_cap,
+                                      uint64_t* coded_bytes_dev, kvtc_stream stream);
+kvtc_status kvtc_entropy_decode_batch(const kvtc_entropy* e, const kvtc_entropy_job* jobs_dev, int n_jobs, int64_t max_tokens,
+                                      const void* coded_base_dev, size_t coded_bytes, void* records_base_dev, size_t records_cap,
+                                      kvtc_stream stream);
 
 /*
  * ---- Positional rotation of keys ----------------------------------------------------------

@@ -100,14 +100,16 @@ def lib() -> C.CDLL:
         L.kvtc_wide_decode.argtypes = [vp, vp, sz, i64, vp, C.c_int, lp, vp, vp]
         for f in (L.kvtc_wide_create, L.kvtc_wide_encode, L.kvtc_wide_decode):
             f.restype = C.c_int
-        L.kvtc_entropy_create.argtypes = [C.POINTER(vp), C.c_int, vp, vp]
+        L.kvtc_entropy_create.argtypes = [C.POINTER(vp), C.c_int, C.c_int, vp, vp]
         L.kvtc_entropy_destroy.argtypes = [vp]
         L.kvtc_entropy_destroy.restype = None
         L.kvtc_entropy_bound.argtypes = [vp, i64]
         L.kvtc_entropy_bound.restype = sz
-        L.kvtc_entropy_encode.argtypes = [vp, vp, i64, vp, sz, vp, vp]
-        L.kvtc_entropy_decode.argtypes = [vp, vp, sz, i64, vp, sz, vp]
-        for f in (L.kvtc_entropy_create, L.kvtc_entropy_encode, L.kvtc_entropy_decode):
+        L.kvtc_entropy_encode.argtypes = [vp, C.c_int, vp, i64, vp, sz, vp, vp]
+        L.kvtc_entropy_decode.argtypes = [vp, C.c_int, vp, sz, i64, vp, sz, vp]
+        L.kvtc_entropy_encode_batch.argtypes = [vp, vp, C.c_int, i64, vp, sz, vp, sz, vp, vp]
+        L.kvtc_entropy_decode_batch.argtypes = [vp, vp, C.c_int, i64, vp, sz, vp, sz, vp]
+        for f in (L.kvtc_entropy_create, L.kvtc_entropy_encode, L.kvtc_entropy_decode, L.kvtc_entropy_encode_batch, L.kvtc_entropy_decode_batch):
             f.restype = C.c_int
         L.kvtc_rope.argtypes = [vp, C.c_int, i64, C.c_int, C.c_int, i64, i64, vp, i64, C.c_double, C.c_int, C.c_int, vp]
         L.kvtc_rope.restype = C.c_int
@@ -387,11 +389,26 @@ class WidePlan:
             pass
 
 
+# layout of kvtc_entropy_job: { int32 table; int32 n_tokens; uint64 records_off; uint64 coded_off; uint64 coded_cap; }
+ENTROPY_JOB_DTYPE = np.dtype([("table", "<i4"), ("n_tokens", "<i4"), ("records_off", "<u8"), ("coded_off", "<u8"), ("coded_cap", "<u8")])
+
+
+def make_entropy_jobs(tables, n_tokens, records_off, coded_off, coded_cap) -> np.ndarray:
+    """A host kvtc_entropy_job table (copy it to the device yourself)."""
+    jobs = np.zeros(len(tables), dtype=ENTROPY_JOB_DTYPE)
+    jobs["table"], jobs["n_tokens"], jobs["records_off"] = tables, n_tokens, records_off
+    jobs["coded_off"], jobs["coded_cap"] = coded_off, coded_cap
+    return jobs
+
+
 def kvtc_entropy_create(record_bytes: int, code_len_host: np.ndarray, stream=None) -> int:
+    """code_len_host: [record_bytes][256] (one table set) or [n_tables][record_bytes][256]."""
     L = np.ascontiguousarray(code_len_host, dtype=np.uint8)
-    assert L.shape == (record_bytes, 256), L.shape
+    if L.ndim == 2:
+        L = L[None]
+    assert L.shape[1:] == (record_bytes, 256), L.shape
     out = C.c_void_p()
-    _check(lib().kvtc_entropy_create(C.byref(out), record_bytes, L.ctypes.data, _stream(stream)))
+    _check(lib().kvtc_entropy_create(C.byref(out), record_bytes, L.shape[0], L.ctypes.data, _stream(stream)))
     return out.value
 
 
@@ -403,16 +420,28 @@ def kvtc_entropy_bound(e: int, n_tokens: int) -> int:
     return lib().kvtc_entropy_bound(e, n_tokens)
 
 
-def kvtc_entropy_encode(e, records_dev, n_tokens: int, out_dev, out_cap: int, out_bytes_dev, stream=None) -> None:
-    _check(lib().kvtc_entropy_encode(e, _ptr(records_dev), n_tokens, _ptr(out_dev), out_cap, _ptr(out_bytes_dev), _stream(stream)))
+def kvtc_entropy_encode(e, records_dev, n_tokens: int, out_dev, out_cap: int, out_bytes_dev, table: int = 0, stream=None) -> None:
+    _check(lib().kvtc_entropy_encode(e, table, _ptr(records_dev), n_tokens, _ptr(out_dev), out_cap, _ptr(out_bytes_dev), _stream(stream)))
 
 
-def kvtc_entropy_decode(e, in_dev, in_bytes: int, n_tokens: int, records_out_dev, out_cap: int, stream=None) -> None:
-    _check(lib().kvtc_entropy_decode(e, _ptr(in_dev), in_bytes, n_tokens, _ptr(records_out_dev), out_cap, _stream(stream)))
+def kvtc_entropy_decode(e, in_dev, in_bytes: int, n_tokens: int, records_out_dev, out_cap: int, table: int = 0, stream=None) -> None:
+    _check(lib().kvtc_entropy_decode(e, table, _ptr(in_dev), in_bytes, n_tokens, _ptr(records_out_dev), out_cap, _stream(stream)))
+
+
+def kvtc_entropy_encode_batch(e, jobs_dev, n_jobs: int, max_tokens: int, records_base_dev, records_bytes: int, coded_base_dev,
+                              coded_cap: int, coded_bytes_dev, stream=None) -> None:
+    _check(lib().kvtc_entropy_encode_batch(e, _ptr(jobs_dev), n_jobs, max_tokens, _ptr(records_base_dev), records_bytes,
+                                           _ptr(coded_base_dev), coded_cap, _ptr(coded_bytes_dev), _stream(stream)))
+
+
+def kvtc_entropy_decode_batch(e, jobs_dev, n_jobs: int, max_tokens: int, coded_base_dev, coded_bytes: int, records_base_dev,
+                              records_cap: int, stream=None) -> None:
+    _check(lib().kvtc_entropy_decode_batch(e, _ptr(jobs_dev), n_jobs, max_tokens, _ptr(coded_base_dev), coded_bytes,
+                                           _ptr(records_base_dev), records_cap, _stream(stream)))
 
 
 class EntropyTables:
-    """Owns a kvtc_entropy handle."""
+    """Owns a kvtc_entropy handle (one or several table sets for records of one size)."""
 
     def __init__(self, record_bytes: int, code_len_host, stream=None):
         self.record_bytes = record_bytes

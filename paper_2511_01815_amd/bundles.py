@@ -30,3 +30,12 @@ def load_tensor_plan_arrays(workload: str, layer: int, kv: str, cr: int) -> Dict
 def cache_plan_arrays(workload: str, n_layers: int, cr: int, kvs: Tuple[str, ...] = ("K", "V")) -> List[Dict[str, np.ndarray]]:
     """All tensors of a cache in job order: layer-major, K before V."""
     return [load_tensor_plan_arrays(workload, l, kv, cr) for l in range(n_layers) for kv in kvs]
+
+
+def entropy_tables(workload: str, cr: int):
+    """Code lengths of the lossless stage, [tensors][record_bytes][256] uint8 in job order, or None when the bundle for
+    this workload and ratio was not written."""
+    path = os.path.join(PLANS_DIR, f"{workload}_entropy_cr{int(cr)}.npz")
+    if not os.path.exists(path):
+        return None
+    return np.load(path)["code_len"]

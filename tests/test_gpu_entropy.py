@@ -93,25 +93,27 @@ def test_entropy_arguments_are_checked_before_any_launch():
     L = kv.lib()
     good = np.full((8, 256), 8, dtype=np.uint8)
     h = C.c_void_p()
-    assert L.kvtc_entropy_create(C.byref(h), 6, good.ctypes.data, None) == 1            # not a multiple of 4
-    assert L.kvtc_entropy_create(C.byref(h), 580, good.ctypes.data, None) == 2          # above the limit
+    assert L.kvtc_entropy_create(C.byref(h), 6, 1, good.ctypes.data, None) == 1            # not a multiple of 4
+    assert L.kvtc_entropy_create(C.byref(h), 580, 1, good.ctypes.data, None) == 2          # above the limit
     bad = good.copy(); bad[3, 7] = 0
-    assert L.kvtc_entropy_create(C.byref(h), 8, bad.ctypes.data, None) == 1             # a length of zero
+    assert L.kvtc_entropy_create(C.byref(h), 8, 1, bad.ctypes.data, None) == 1             # a length of zero
     bad = good.copy(); bad[2, :3] = 1
-    assert L.kvtc_entropy_create(C.byref(h), 8, bad.ctypes.data, None) == 1             # Kraft sum above one
+    assert L.kvtc_entropy_create(C.byref(h), 8, 1, bad.ctypes.data, None) == 1             # Kraft sum above one
     assert "prefix code" in kv.kvtc_last_error()
     tab = kv.EntropyTables(8, good)
     buf = torch.zeros(4096, dtype=torch.uint8, device=DEV)
     n = torch.zeros(1, dtype=torch.int64, device=DEV)
     p = buf.data_ptr()
-    assert L.kvtc_entropy_encode(tab.handle, p, 10, p + 1024, 8, n.data_ptr(), None) == 3     # no room for the directory
-    assert L.kvtc_entropy_encode(tab.handle, p + 2, 10, p + 1024, 2048, n.data_ptr(), None) == 1
-    assert L.kvtc_entropy_encode(tab.handle, p, 10, p + 1024, 2048, None, None) == 1
-    assert L.kvtc_entropy_decode(tab.handle, p, 8, 10, p + 1024, 80, None) == 3               # container shorter than its directory
-    assert L.kvtc_entropy_decode(tab.handle, p, 1024, 10, p + 1024, 79, None) == 3
-    assert L.kvtc_entropy_decode(tab.handle, p, 1024, 0, None, 0, None) == 0
+    assert L.kvtc_entropy_encode(tab.handle, 0, p, 10, p + 1024, 8, n.data_ptr(), None) == 3     # no room for the directory
+    assert L.kvtc_entropy_encode(tab.handle, 0, p + 2, 10, p + 1024, 2048, n.data_ptr(), None) == 1
+    assert L.kvtc_entropy_encode(tab.handle, 0, p, 10, p + 1024, 2048, None, None) == 1
+    assert L.kvtc_entropy_decode(tab.handle, 0, p, 8, 10, p + 1024, 80, None) == 3               # container shorter than its directory
+    assert L.kvtc_entropy_decode(tab.handle, 0, p, 1024, 10, p + 1024, 79, None) == 3
+    assert L.kvtc_entropy_decode(tab.handle, 0, p, 1024, 0, None, 0, None) == 0
+    assert L.kvtc_entropy_encode(tab.handle, 1, p, 10, p + 1024, 2048, n.data_ptr(), None) == 1             # one table set only
+    assert L.kvtc_entropy_create(C.byref(h), 8, 0, good.ctypes.data, None) == 1
     # a container of zeros (a damaged one: every offset zero) decodes to something without a fault
-    assert L.kvtc_entropy_decode(tab.handle, p, 1024, 10, p + 2048, 80, None) == 0
+    assert L.kvtc_entropy_decode(tab.handle, 0, p, 1024, 10, p + 2048, 80, None) == 0
     torch.cuda.synchronize()
     tab.close()
 
@@ -157,3 +159,53 @@ def test_full_size_round_trip_of_a_gpu_coded_tensor():
     print(f"32768 tokens at 16x: {T * R} -> {nb} bytes, lossless ratio {T * R / nb:.3f} (total {2048 * T / nb:.2f}x)")
     tab.close()
     plan.close()
+
+
+def test_batched_jobs_equal_single_calls_and_bad_jobs_are_left_alone():
+    """Four tensors in one call: two table sets, ragged lengths, containers at ragged (4-byte aligned) offsets; a fifth job
+    names a table set that does not exist and a sixth is longer than max_tokens: both are reported and nothing of theirs
+    is touched."""
+    recs = [_records("c2_K_cr16", 300, ks.TEST_DRAW), _records("c2_V_cr16", 129, ks.TEST_DRAW),
+            _records("c2_K_cr16", 64, 7), _records("c2_V_cr16", 1, 8)]
+    tabs = np.stack([ke.calibrate_tables(_records("c2_K_cr16", 512, ks.CALIB_DRAW)), ke.calibrate_tables(_records("c2_V_cr16", 512, ks.CALIB_DRAW))])
+    table_of = [0, 1, 0, 1]
+    R = 128
+    tab = kv.EntropyTables(R, tabs)
+    refs = [ke.encode(r, tabs[t]) for r, t in zip(recs, table_of)]
+    n_tok = [r.shape[0] for r in recs] + [10, 400]
+    rec_off, pos = [], 0
+    for n in n_tok:
+        rec_off.append(pos)
+        pos += n * R
+    rec_all = np.full(pos, 0x11, dtype=np.uint8)
+    for r, o in zip(recs, rec_off):
+        rec_all[o:o + r.size] = r.reshape(-1)
+    caps = [ke.bound_bytes(n, R) + 4 * i for i, n in enumerate(n_tok)]        # ragged room
+    cod_off = np.concatenate([[0], np.cumsum(caps)[:-1]]).tolist()
+    total = int(sum(caps))
+    jobs = kv.make_entropy_jobs(table_of + [5, 0], n_tok, rec_off, cod_off, caps)
+    jd = torch.from_numpy(jobs.view(np.uint8)).to(DEV)
+    rd = torch.from_numpy(rec_all).to(DEV)
+    coded = torch.full((total + 64,), 0xA5, dtype=torch.uint8, device=DEV)
+    sizes = torch.zeros(6, dtype=torch.int64, device=DEV)
+    kv.kvtc_entropy_encode_batch(tab.handle, jd, 6, 300, rd, rec_all.size, coded, total, sizes)
+    torch.cuda.synchronize()
+    c = coded.cpu().numpy()
+    sz = sizes.cpu().numpy().view(np.uint64)
+    assert sz[4] == sz[5] == np.uint64(2 ** 64 - 1)
+    assert np.all(c[cod_off[4]:] == 0xA5), "a rejected job's room (or the guard) was written"
+    for i, ref in enumerate(refs):
+        assert int(sz[i]) == len(ref)
+        assert c[cod_off[i]:cod_off[i] + len(ref)].tobytes() == ref
+        assert np.all(c[cod_off[i] + ke.bound_bytes(n_tok[i], R):cod_off[i] + caps[i]] == 0xA5)
+    # decode: the containers' true lengths as coded_cap
+    jobs2 = kv.make_entropy_jobs(table_of + [5, 0], n_tok, rec_off, cod_off, [len(r) for r in refs] + [caps[4], caps[5]])
+    jd2 = torch.from_numpy(jobs2.view(np.uint8)).to(DEV)
+    back = torch.full((rec_all.size + 64,), 0x5A, dtype=torch.uint8, device=DEV)
+    kv.kvtc_entropy_decode_batch(tab.handle, jd2, 6, 300, coded, total, back, rec_all.size)
+    torch.cuda.synchronize()
+    b = back.cpu().numpy()
+    for r, o in zip(recs, rec_off):
+        assert np.array_equal(b[o:o + r.size], r.reshape(-1))
+    assert np.all(b[rec_off[4]:] == 0x5A), "a rejected job's records (or the guard) were written"
+    tab.close()
