@@ -117,3 +117,21 @@ def test_position_tables_beat_a_position_blind_code_on_structured_records():
     blind = ke.limited_lengths(np.bincount(rec.reshape(-1), minlength=256))
     one_table = sum(int(blind[b]) for b in rec.reshape(-1)) / T
     assert per_pos < 10.0 < one_table
+
+
+def test_committed_table_bundle_is_what_the_script_writes():
+    """The code-length tables the benchmark loads are stored values: for two tensors of the 32-layer cache they must be
+    exactly what oracle/make_entropy_tables.py computes, and every table must be a prefix code of at most 12 bits."""
+    import importlib.util
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("make_entropy_tables", os.path.join(root, "oracle", "make_entropy_tables.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    z = np.load(os.path.join(root, "paper_2511_01815_amd", "plans", "c3_entropy_cr16.npz"))["code_len"]
+    assert z.shape == (64, 128, 256) and z.dtype == np.uint8
+    assert z.min() >= 1 and z.max() <= ke.MAX_LEN
+    kraft = (2.0 ** -z.astype(np.float64)).sum(axis=2)
+    assert np.all(kraft <= 1.0 + 1e-12)
+    np.testing.assert_array_equal(z[0], mod.tables_of(0, 0))           # layer 0, K
+    np.testing.assert_array_equal(z[63], mod.tables_of(31, 1))         # layer 31, V
