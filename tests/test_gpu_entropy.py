@@ -209,3 +209,20 @@ def test_batched_jobs_equal_single_calls_and_bad_jobs_are_left_alone():
         assert np.array_equal(b[o:o + r.size], r.reshape(-1))
     assert np.all(b[rec_off[4]:] == 0x5A), "a rejected job's records (or the guard) were written"
     tab.close()
+
+
+@pytest.mark.parametrize("R,T", [(576, 130), (544, 64), (4, 1000), (36, 4097)])
+def test_record_sizes_at_the_limits(R, T):
+    """The largest record the stage takes (576 bytes: one wave per workgroup, 129 KB of LDS), the full-rank plans' 544, the
+    smallest (4) and a size that is no power of two; synthetic bytes with a different skew at every position, tables from
+    half of them."""
+    rng = np.random.default_rng(R + T)
+    rec = np.stack([np.minimum(255, rng.geometric(1.0 / (2 + (7 * k) % 90), T) - 1) for k in range(R)], axis=1).astype(np.uint8)
+    lengths = ke.calibrate_tables(rec[:T // 2])
+    tab = kv.EntropyTables(R, lengths)
+    ref = ke.encode(rec, lengths)
+    out, n, bound = _gpu_encode(tab, rec)
+    assert n == len(ref) and out[:n].tobytes() == ref
+    assert np.all(out[bound:] == 0xA5)
+    assert np.array_equal(_gpu_decode(tab, ref, T, R), rec)
+    tab.close()
