@@ -340,6 +340,27 @@ kvtc_status kvtc_entropy_decode_batch(const kvtc_entropy* e, const kvtc_entropy_
                                       kvtc_stream stream);
 
 /*
+ * ---- Calibration: the error table of the bit allocation ----------------------------------------
+ * (paper, Section "Quantization" and appendix "Dynamic programming algorithm": the dynamic programme
+ * chooses, per block of subsequent PCA coordinates, a quantiser type by the error it causes on the
+ * calibration data.)  Computes, for every candidate block (start, n) and every width b = 1..max_bits, the
+ * change of the squared error against dropping the block,
+ *     change[block][b - 1] = sum over tokens t and coordinates j of the block of (d - d_hat)^2 - d^2,
+ * where d_hat is d after the coder's own quantiser at width b (shared fp16 shift rounded down and scale
+ * rounded up per token and block, code decided in fp32, exactly as kvtc_encode decides it).  The heavy
+ * part of calibration after the PCA: every (block, width) pair is a pass over the calibration tokens.
+ *   coef_dev    [n_tokens][ld] fp32: the calibration coefficients P = (C - mu) V (device, 4-byte aligned)
+ *   blocks_dev  n_blocks x {start, n} (device): 1 <= n <= 1024, start + n <= ld; a block outside these
+ *               limits gets NaN in its row of the result (the list is not visible to the host)
+ *   change_dev  [n_blocks][max_bits] fp64 (device, 8-byte aligned); max_bits in 1..8
+ * One workgroup per block with fixed summation order: results are reproducible.  No allocation, no
+ * synchronisation.  The PCA itself (an eigen-decomposition of a p x p matrix) is not part of this library.
+ */
+typedef struct { int32_t start; int32_t n; } kvtc_calib_block;
+kvtc_status kvtc_calib_block_errors(const float* coef_dev, int64_t n_tokens, int64_t ld, const kvtc_calib_block* blocks_dev,
+                                    int n_blocks, int max_bits, double* change_dev, kvtc_stream stream);
+
+/*
  * ---- Positional rotation of keys ----------------------------------------------------------
  * (paper, Section "Feature decorrelation": the rotary positional embedding is removed from keys
  * before they are transform-coded, because it hides their low-rank structure, and decoded keys are

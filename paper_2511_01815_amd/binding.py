@@ -111,6 +111,8 @@ def lib() -> C.CDLL:
         L.kvtc_entropy_decode_batch.argtypes = [vp, vp, C.c_int, i64, vp, sz, vp, sz, vp]
         for f in (L.kvtc_entropy_create, L.kvtc_entropy_encode, L.kvtc_entropy_decode, L.kvtc_entropy_encode_batch, L.kvtc_entropy_decode_batch):
             f.restype = C.c_int
+        L.kvtc_calib_block_errors.argtypes = [vp, i64, i64, vp, C.c_int, C.c_int, vp, vp]
+        L.kvtc_calib_block_errors.restype = C.c_int
         L.kvtc_rope.argtypes = [vp, C.c_int, i64, C.c_int, C.c_int, i64, i64, vp, i64, C.c_double, C.c_int, C.c_int, vp]
         L.kvtc_rope.restype = C.c_int
         L.kvtc_last_error.argtypes = []
@@ -457,6 +459,11 @@ class EntropyTables:
             self.close()
         except Exception:
             pass
+
+
+def kvtc_calib_block_errors(coef_dev, n_tokens: int, ld: int, blocks_dev, n_blocks: int, max_bits: int, change_dev, stream=None) -> None:
+    """blocks_dev: device array of int32 pairs (start, n); change_dev: [n_blocks][max_bits] float64 on the device."""
+    _check(lib().kvtc_calib_block_errors(_ptr(coef_dev), n_tokens, ld, _ptr(blocks_dev), n_blocks, max_bits, _ptr(change_dev), _stream(stream)))
 
 
 class Batch:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvtc.so")
-SOURCES = ["kvtc_api.hip", "kvtc_encode.hip", "kvtc_decode.hip", "kvtc_fp8.hip", "kvtc_rope.hip", "kvtc_probe.hip", "kvtc_entropy.hip"]
+SOURCES = ["kvtc_api.hip", "kvtc_encode.hip", "kvtc_decode.hip", "kvtc_fp8.hip", "kvtc_rope.hip", "kvtc_probe.hip", "kvtc_entropy.hip", "kvtc_calib.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
