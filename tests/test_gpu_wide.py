@@ -116,6 +116,21 @@ def test_four_layers_under_one_basis_at_16x():
     _check_wide(oplan, X, 4, "wide-4layers", hdr_bar=5e-2)
 
 
+def test_eight_layers_four_sections():
+    """Eight layers (p = 8192), 4096 kept coordinates in sixteen groups of 256 = four full sections, a basis that is not
+    orthonormal (the coder does not need it to be): three sections are added to the first one's output, and a token's
+    features are gathered from eight tensors."""
+    p, T, r = 8192, 600, 4096
+    rng = np.random.default_rng(21)
+    V = (rng.standard_normal((p, r)) / np.sqrt(p)).astype(np.float32)
+    mu = rng.normal(0, 0.1, p)
+    blocks = [ko.Block(256 * i, 256, 2 + i % 4) for i in range(16)]
+    oplan = ko.compile_plan(mu, V, blocks)
+    assert [s_.r for s_ in kw.sections_of(oplan)] == [1024] * 4
+    X = ko.bf16_round((rng.standard_normal((T, p)) * np.linspace(2.0, 0.2, p) + mu).astype(np.float32))
+    _check_wide(oplan, X, 8, "wide-8layers")
+
+
 def test_wide_arguments_are_checked_before_any_launch():
     p = 256
     rng = np.random.default_rng(2)
