@@ -50,20 +50,22 @@ __host__ __device__ inline uint32_t chunk_image_dwords(int R) { return (uint32_t
 __host__ __device__ inline uint32_t row_stride_dwords(int R) { return (uint32_t)R / 4u + 1u; }
 __host__ __device__ inline uint64_t header_bytes(int64_t n_chunks) { return 4ull * (uint64_t)(n_chunks + 1) + 2ull * kChunk * (uint64_t)n_chunks; }
 
-// LDS of a launch: per wave the chunk's image and its rows, then (decode) 64 bytes of tables per byte position.
-// Waves per workgroup: the count (1..4) that lets the most waves share a compute unit's 160 KB -- a wave alone on its SIMD
-// has nothing to hide its LDS and arithmetic latencies behind.
-inline size_t lds_bytes(int R, int waves, bool with_tables) {
-    return (size_t)waves * ((size_t)chunk_image_dwords(R) * 4 + (size_t)kChunk * row_stride_dwords(R) * 4) + (with_tables ? (size_t)R * 64 : 0);
+// LDS of a launch.  The kernel that writes the code strings holds, per wave, the chunk's image (worst case) and its rows;
+// the decoder its rows and, per workgroup, 64 bytes of tables per byte position.  Waves per workgroup: the count (1..4) that
+// lets the most waves share a compute unit's 160 KB -- a wave alone on its SIMD has nothing to hide its latencies behind.
+inline size_t lds_bytes(int R, int waves, bool decode) {
+    const size_t rows = (size_t)kChunk * row_stride_dwords(R) * 4;
+    return decode ? (size_t)waves * rows + (size_t)R * 64 : (size_t)waves * ((size_t)chunk_image_dwords(R) * 4 + rows);
 }
-inline int waves_per_wg(int R, bool with_tables) {
+inline int waves_per_wg(int R, bool decode) {
     int best = 1;
     size_t best_cu = 0;
     for (int n = 1; n <= 4; ++n) {
-        const size_t b = lds_bytes(R, n, with_tables);
+        const size_t b = lds_bytes(R, n, decode);
         if (b > 150u * 1024u) break;
-        const size_t per_cu = ((size_t)kLdsBudget / b) * n;
-        if (per_cu > best_cu) { best_cu = per_cu; best = n; }
+        size_t wgs = (size_t)kLdsBudget / b;
+        if (wgs * n > 32) wgs = 32 / n;                 // a compute unit holds 32 waves at most
+        if (wgs * n > best_cu) { best_cu = wgs * n; best = n; }
     }
     return best;
 }
@@ -281,9 +283,11 @@ __global__ void __launch_bounds__(256) entropy_write_kernel(const EntropyArgs a)
     }
 }
 
-// decode: one wave per chunk.  Every read of the container is clamped to the job's bytes and to the chunk's image, so a
-// damaged container gives wrong bytes, never a fault.  LDS: the waves' images and rows, then the job's limits and rank
-// offsets of every byte position (64 bytes each; the workgroup's chunks belong to one job).
+// decode: one wave per chunk.  Every read of the container is clamped to the job's bytes, so a damaged container gives
+// wrong bytes, never a fault.  A lane reads its own bit string straight from the container, one dword ahead of need: the
+// strings of a chunk's tokens follow each other, so the wave's reads fall on a few lines that stay in the L1.  LDS: the waves'
+// output rows, then the job's limits and rank offsets of every byte position (64 bytes each; the workgroup's chunks belong to
+// one job) -- no image of the chunk, which would halve the waves a compute unit can hold.
 __global__ void __launch_bounds__(256) entropy_decode_kernel(const EntropyArgs a) {
     extern __shared__ uint32_t lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
@@ -291,32 +295,26 @@ __global__ void __launch_bounds__(256) entropy_decode_kernel(const EntropyArgs a
     const JobView v = job_view(a, blockIdx.y);
     const int64_t chunk = (int64_t)blockIdx.x * n_waves + wave;
     const bool live = v.ok && chunk < v.n_chunks;
-    const uint32_t img_dw = chunk_image_dwords(R), rs = row_stride_dwords(R);
-    uint32_t* img = lds + (size_t)wave * (img_dw + kChunk * rs);
-    uint32_t* rows = img + img_dw;
-    uint32_t* tab = lds + (size_t)n_waves * (img_dw + kChunk * rs);          // [R][16] dwords: limit[16] u16, off[16] i16
+    const uint32_t rs = row_stride_dwords(R);
+    uint32_t* rows = lds + (size_t)wave * kChunk * rs;
+    uint32_t* tab = lds + (size_t)n_waves * kChunk * rs;          // [R][16] dwords: limit[16] u16, off[16] i16
     if (v.ok) {
         for (int i = threadIdx.x; i < R * 16; i += blockDim.x)
             tab[i] = reinterpret_cast<const uint32_t*>(v.dec + (i >> 4))[i & 15];
     }
-    uint32_t n_dw = 0;
+    __syncthreads();
     if (live) {
         uint64_t begin = v.chunk_off[chunk], end = v.chunk_off[chunk + 1];
         begin = begin < v.payload_cap ? begin : v.payload_cap;
         end = end < begin ? begin : (end < v.payload_cap ? end : v.payload_cap);
-        n_dw = (uint32_t)((end - begin) / 4u);
-        n_dw = n_dw < img_dw ? n_dw : img_dw;
+        const uint32_t n_dw = (uint32_t)((end - begin) / 4u);
         const uint32_t* src = reinterpret_cast<const uint32_t*>(v.payload + (begin & ~3ull));
-        for (uint32_t i = lane; i < n_dw; i += 64) img[i] = src[i];
-    }
-    __syncthreads();
-    if (live) {
         const int64_t t = chunk * kChunk + lane;
         const uint32_t pos = wave_exclusive_scan((uint32_t)v.len_bits[t]);
         if (t < v.T) {
             uint32_t* my = rows + (uint32_t)lane * rs;
-            auto word = [&](uint32_t i) { return i < n_dw ? img[i] : 0u; };
-            // the next bits of the string in a register; the image is read a dword ahead of need
+            auto word = [&](uint32_t i) { return i < n_dw ? src[i] : 0u; };
+            // the next bits of the string in a register; the container is read a dword ahead of need
             uint32_t idx = (pos >> 5) + 2u;
             uint64_t buf = (((uint64_t)word(idx - 1u) << 32) | word(idx - 2u)) >> (pos & 31u);
             uint32_t nbuf = 64u - (pos & 31u);
