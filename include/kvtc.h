@@ -361,6 +361,23 @@ kvtc_status kvtc_calib_block_errors(const float* coef_dev, int64_t n_tokens, int
                                     int n_blocks, int max_bits, double* change_dev, kvtc_stream stream);
 
 /*
+ * Calibration: the one pass over the calibration tokens that the PCA needs (paper, Section "Feature
+ * decorrelation", eq. 2: the mean and the SVD of the centred calibration matrix C - mu; the right singular
+ * vectors are the eigenvectors of the centred second-moment matrix).  Computes, in double precision and
+ * with a fixed summation order (token by token),
+ *     sum_dev[f]      = sum over tokens of x[t][f]
+ *     gram_dev[f][g]  = sum over tokens of x[t][f] * x[t][g]          (all p x p entries)
+ * from which the caller forms mu = sum / n and the covariance gram / n - mu mu^T and decomposes it on the
+ * host (a p x p eigen-problem, not part of this library).
+ *   x_dev, dtype, layout  the calibration tokens as kvtc_encode_blocked takes them (per-layer tensors or
+ *                         heads-major caches in place); p a multiple of 64
+ *   sum_dev [p], gram_dev [p][p]  device, 8-byte aligned
+ * No allocation, no synchronisation.
+ */
+kvtc_status kvtc_calib_moments(const void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int p, const kvtc_layout* layout,
+                               double* sum_dev, double* gram_dev, kvtc_stream stream);
+
+/*
  * ---- Positional rotation of keys ----------------------------------------------------------
  * (paper, Section "Feature decorrelation": the rotary positional embedding is removed from keys
  * before they are transform-coded, because it hides their low-rank structure, and decoded keys are

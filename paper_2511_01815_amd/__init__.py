@@ -17,7 +17,7 @@ from .binding import (  # noqa: F401
     kvtc_wide_encoded_bytes, kvtc_wide_encode, kvtc_wide_decode,
     EntropyTables, kvtc_entropy_create, kvtc_entropy_destroy, kvtc_entropy_bound, kvtc_entropy_encode, kvtc_entropy_decode,
     kvtc_entropy_encode_batch, kvtc_entropy_decode_batch, make_entropy_jobs, ENTROPY_JOB_DTYPE,
-    kvtc_calib_block_errors,
+    kvtc_calib_block_errors, kvtc_calib_moments,
     KvtcLayout, layout, kvtc_encode_blocked, kvtc_decode_blocked, kvtc_encode_batch_blocked, kvtc_decode_batch_blocked,
 )
 from . import bundles  # noqa: F401

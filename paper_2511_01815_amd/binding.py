@@ -113,6 +113,8 @@ def lib() -> C.CDLL:
             f.restype = C.c_int
         L.kvtc_calib_block_errors.argtypes = [vp, i64, i64, vp, C.c_int, C.c_int, vp, vp]
         L.kvtc_calib_block_errors.restype = C.c_int
+        L.kvtc_calib_moments.argtypes = [vp, C.c_int, i64, C.c_int, lp, vp, vp, vp]
+        L.kvtc_calib_moments.restype = C.c_int
         L.kvtc_rope.argtypes = [vp, C.c_int, i64, C.c_int, C.c_int, i64, i64, vp, i64, C.c_double, C.c_int, C.c_int, vp]
         L.kvtc_rope.restype = C.c_int
         L.kvtc_last_error.argtypes = []
@@ -464,6 +466,10 @@ class EntropyTables:
 def kvtc_calib_block_errors(coef_dev, n_tokens: int, ld: int, blocks_dev, n_blocks: int, max_bits: int, change_dev, stream=None) -> None:
     """blocks_dev: device array of int32 pairs (start, n); change_dev: [n_blocks][max_bits] float64 on the device."""
     _check(lib().kvtc_calib_block_errors(_ptr(coef_dev), n_tokens, ld, _ptr(blocks_dev), n_blocks, max_bits, _ptr(change_dev), _stream(stream)))
+
+
+def kvtc_calib_moments(x_dev, dtype: int, n_tokens: int, p: int, lay, sum_dev, gram_dev, stream=None) -> None:
+    _check(lib().kvtc_calib_moments(_ptr(x_dev), dtype, n_tokens, p, C.byref(lay), _ptr(sum_dev), _ptr(gram_dev), _stream(stream)))
 
 
 class Batch:

@@ -33,6 +33,8 @@ struct RopeArgs {
     double theta[128];
 };
 hipError_t launch_rope(const RopeArgs& a, kvtc_dtype dtype, int interleaved, int grid, hipStream_t stream);
+hipError_t launch_calib_moments(const void* x, kvtc_dtype dtype, int64_t n_tokens, int p, int64_t ld, int blk_log2, int64_t blk_jump,
+                                double* sum, double* gram, hipStream_t stream);
 int decode_rec_bytes(int tt, int rec_dwords);
 int decode_ring_bytes(int nct);
 int decode_stage_u4(int nct);
@@ -1139,6 +1141,22 @@ kvtc_status kvtc_wide_decode(const kvtc_wide* w, const void* in_dev, size_t in_b
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_wide_decode: launch failed: %s", hipGetErrorString(e));
     }
+    return KVTC_OK;
+}
+
+kvtc_status kvtc_calib_moments(const void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int p, const kvtc_layout* layout, double* sum_dev,
+                               double* gram_dev, kvtc_stream stream) {
+    if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_calib_moments: n_tokens=%lld", (long long)n_tokens);
+    if (p <= 0 || p % 64 != 0) return fail(KVTC_E_ARG, "kvtc_calib_moments: p=%d must be a positive multiple of 64", p);
+    if (!x_dev || !sum_dev || !gram_dev) return fail(KVTC_E_ARG, "kvtc_calib_moments: null buffer");
+    if ((reinterpret_cast<uintptr_t>(sum_dev) & 7u) || (reinterpret_cast<uintptr_t>(gram_dev) & 7u))
+        return fail(KVTC_E_ARG, "kvtc_calib_moments: outputs must be 8-byte aligned");
+    XLayout xl;
+    kvtc_status st = check_layout("kvtc_calib_moments", x_dev, dtype, layout, p, n_tokens, &xl);
+    if (st != KVTC_OK) return st;
+    const hipError_t e = launch_calib_moments(x_dev, dtype, n_tokens, p, xl.ld, xl.blk_log2, xl.blk_jump, sum_dev, gram_dev,
+                                              static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_calib_moments: launch failed: %s", hipGetErrorString(e));
     return KVTC_OK;
 }
 

@@ -10,6 +10,11 @@
 // every width is evaluated from the same registers with the coder's own scalar numerics (fp16 shift
 // rounded down, scale rounded up, code by subtract, multiply by the rounded reciprocal, round to
 // even, clamp).  Errors are accumulated in double from exactly representable terms.
+//
+// Also here: the first and second moments of the calibration tokens (sum of x and sum of x x^T, in
+// double), the one pass over the calibration data that the PCA needs (paper, Section "Feature
+// decorrelation", eq. 2: mean and SVD of the centred matrix; its right singular vectors are the
+// eigenvectors of the centred second-moment matrix, which the caller forms and decomposes on the host).
 #include <hip/hip_runtime.h>
 
 #include "kvtc_dev.h"
@@ -117,6 +122,87 @@ __global__ void __launch_bounds__(kCalibThreads) calib_block_errors_kernel(const
     }
 }
 
+
+// ---- moments ------------------------------------------------------------------------------------
+constexpr int kGramTile = 64;      // a workgroup owns a 64 x 64 tile of the second-moment matrix, a thread 4 x 4 of it
+constexpr int kGramTokens = 32;    // tokens staged per step
+
+template <typename XT> __device__ __forceinline__ double load_as_double(const XT* p);
+template <> __device__ __forceinline__ double load_as_double<uint16_t>(const uint16_t* p) { return (double)bits_f32((uint32_t)*p << 16); }
+template <> __device__ __forceinline__ double load_as_double<float>(const float* p) { return (double)*p; }
+
+// element offset of feature f inside a token (blocks of 2^blk_log2 features lie blk_jump elements apart; 0 = contiguous)
+__device__ __forceinline__ int64_t feature_offset(int f, int blk_log2, int64_t blk_jump) {
+    return (int64_t)f + (blk_log2 ? (int64_t)(f >> blk_log2) * blk_jump : (int64_t)0);
+}
+
+template <typename XT>
+__global__ void __launch_bounds__(256) calib_sum_kernel(const XT* x, int64_t n_tokens, int p, int64_t ld, int blk_log2, int64_t blk_jump, double* sum) {
+    const int f = blockIdx.x * 256 + threadIdx.x;
+    if (f >= p) return;
+    const XT* col = x + feature_offset(f, blk_log2, blk_jump);
+    double s = 0.0;
+    for (int64_t t = 0; t < n_tokens; ++t) s += load_as_double<XT>(col + t * ld);       // token order: a fixed sum
+    sum[f] = s;
+}
+
+template <typename XT>
+__global__ void __launch_bounds__(256) calib_gram_kernel(const XT* x, int64_t n_tokens, int p, int64_t ld, int blk_log2, int64_t blk_jump, double* gram) {
+    __shared__ double a[kGramTokens][kGramTile], b[kGramTokens][kGramTile];
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    const int i0 = blockIdx.y * kGramTile, j0 = blockIdx.x * kGramTile;
+    double acc[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[r][c] = 0.0;
+    for (int64_t t0 = 0; t0 < n_tokens; t0 += kGramTokens) {
+#pragma unroll
+        for (int k = 0; k < kGramTokens * kGramTile / 256; ++k) {
+            const int e = tid + k * 256, tt = e / kGramTile, ff = e % kGramTile;
+            const int64_t t = t0 + tt;
+            const bool in = t < n_tokens;
+            a[tt][ff] = in ? load_as_double<XT>(x + t * ld + feature_offset(i0 + ff, blk_log2, blk_jump)) : 0.0;
+            b[tt][ff] = in ? load_as_double<XT>(x + t * ld + feature_offset(j0 + ff, blk_log2, blk_jump)) : 0.0;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int tt = 0; tt < kGramTokens; ++tt) {
+            double ra[4], rb[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) { ra[r] = a[tt][ty * 4 + r]; rb[r] = b[tt][tx * 4 + r]; }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[r][c] = __builtin_fma(ra[r], rb[c], acc[r][c]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) gram[(size_t)(i0 + ty * 4 + r) * p + (j0 + tx * 4 + c)] = acc[r][c];
+}
+
+}  // namespace
+
+namespace kvtc {
+// x: n_tokens tokens of p features (p a multiple of 64) at the given layout; sum [p], gram [p][p]
+hipError_t launch_calib_moments(const void* x, kvtc_dtype dtype, int64_t n_tokens, int p, int64_t ld, int blk_log2, int64_t blk_jump,
+                                double* sum, double* gram, hipStream_t stream) {
+    const dim3 gs((unsigned)((p + 255) / 256)), gg((unsigned)(p / kGramTile), (unsigned)(p / kGramTile));
+    if (dtype == KVTC_BF16) {
+        hipLaunchKernelGGL(calib_sum_kernel<uint16_t>, gs, dim3(256), 0, stream, static_cast<const uint16_t*>(x), n_tokens, p, ld, blk_log2, blk_jump, sum);
+        hipLaunchKernelGGL(calib_gram_kernel<uint16_t>, gg, dim3(256), 0, stream, static_cast<const uint16_t*>(x), n_tokens, p, ld, blk_log2, blk_jump, gram);
+    } else {
+        hipLaunchKernelGGL(calib_sum_kernel<float>, gs, dim3(256), 0, stream, static_cast<const float*>(x), n_tokens, p, ld, blk_log2, blk_jump, sum);
+        hipLaunchKernelGGL(calib_gram_kernel<float>, gg, dim3(256), 0, stream, static_cast<const float*>(x), n_tokens, p, ld, blk_log2, blk_jump, gram);
+    }
+    return hipGetLastError();
+}
+}  // namespace kvtc
+
+namespace {
 }  // namespace
 
 extern "C" {

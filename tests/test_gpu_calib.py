@@ -92,3 +92,58 @@ def test_bad_blocks_and_arguments():
     assert L.kvtc_calib_block_errors(p, -1, 64, blocks.data_ptr(), 5, 2, out.data_ptr(), None) == 1
     assert L.kvtc_calib_block_errors(None, 10, 64, blocks.data_ptr(), 5, 2, out.data_ptr(), None) == 1
     assert L.kvtc_calib_block_errors(p, 10, 64, blocks.data_ptr(), 0, 2, out.data_ptr(), None) == 0
+
+
+def test_moments_give_the_oracles_pca():
+    """Sum and second moments of a calibration draw on the GPU (bf16 tokens, token-major and heads-major), against NumPy in
+    float64; the eigen-decomposition of the covariance formed from them against the oracle's SVD-based PCA."""
+    L = ks.make_layer(ks.layer_spec("c2", 0, 0))
+    n, p = 3000, 1024
+    bits = ks.draw_bf16(L, n, ks.CALIB_DRAW)
+    C_ = ks.bf16_bits_to_f32(bits).astype(np.float64)
+    xd = torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)            # [n, 1024]
+    s = torch.zeros(p, dtype=torch.float64, device=DEV)
+    g = torch.zeros((p, p), dtype=torch.float64, device=DEV)
+    kv.kvtc_calib_moments(xd, kv.KVTC_BF16, n, p, kv.layout(p), s, g)
+    xh = xd.reshape(n, 8, 128).permute(1, 0, 2).contiguous()                            # [8][n][128]
+    s2 = torch.zeros_like(s)
+    g2 = torch.zeros_like(g)
+    kv.kvtc_calib_moments(xh, kv.KVTC_BF16, n, p, kv.layout(128, 128, n * 128), s2, g2)
+    torch.cuda.synchronize()
+    assert torch.equal(s, s2) and torch.equal(g, g2)                                     # same sums in the same order
+    S_, G_ = s.cpu().numpy(), g.cpu().numpy()
+    ref_s, ref_g = C_.sum(axis=0), C_.T @ C_
+    assert np.max(np.abs(S_ - ref_s)) <= 1e-12 * np.abs(C_).sum(axis=0).max()
+    assert np.max(np.abs(G_ - ref_g)) <= 1e-12 * np.abs(ref_g).max()
+    assert np.array_equal(G_, G_.T)
+    # PCA from the moments (host: a 1024 x 1024 eigen-problem) against the oracle's SVD of the centred matrix
+    mu = S_ / n
+    lam, W = np.linalg.eigh(G_ / n - np.outer(mu, mu))
+    lam, W = lam[::-1], W[:, ::-1]
+    mu_o, V_o, S_o = ko.pca(C_)
+    assert np.max(np.abs(mu - mu_o)) <= 1e-14
+    k = 300                                                                              # beyond what any calibrated plan keeps at 16x
+    assert np.max(np.abs(lam[:k] * n / S_o[:k] ** 2 - 1.0)) <= 1e-7
+    dots = np.abs(np.sum(W[:, :k] * V_o[:, :k], axis=0))
+    assert dots.min() >= 1.0 - 1e-6, dots.min()
+
+
+def test_moments_fp32_input_and_arguments():
+    L = ks.make_layer(ks.layer_spec("c1", 0, 0))
+    n, p = 515, 128
+    X = ks.draw_f32(L, n, ks.CALIB_DRAW)
+    xd = torch.from_numpy(X).to(DEV)
+    s = torch.zeros(p, dtype=torch.float64, device=DEV)
+    g = torch.zeros((p, p), dtype=torch.float64, device=DEV)
+    kv.kvtc_calib_moments(xd, kv.KVTC_F32, n, p, kv.layout(p), s, g)
+    torch.cuda.synchronize()
+    X64 = X.astype(np.float64)
+    assert np.max(np.abs(s.cpu().numpy() - X64.sum(axis=0))) <= 1e-12 * np.abs(X64).sum(axis=0).max()
+    assert np.max(np.abs(g.cpu().numpy() - X64.T @ X64)) <= 1e-12 * np.abs(X64.T @ X64).max()
+    lib = kv.lib()
+    lay = kv.layout(p)
+    assert lib.kvtc_calib_moments(xd.data_ptr(), 1, n, 100, C.byref(lay), s.data_ptr(), g.data_ptr(), None) == 1      # p not a multiple of 64
+    assert lib.kvtc_calib_moments(xd.data_ptr(), 1, n, p, None, s.data_ptr(), g.data_ptr(), None) == 1
+    assert lib.kvtc_calib_moments(xd.data_ptr(), 1, n, p, C.byref(lay), None, g.data_ptr(), None) == 1
+    short = kv.layout(64)
+    assert lib.kvtc_calib_moments(xd.data_ptr(), 1, n, p, C.byref(short), s.data_ptr(), g.data_ptr(), None) == 1       # pitch below p
