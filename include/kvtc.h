@@ -265,12 +265,13 @@ kvtc_status kvtc_decode_batch_blocked(const kvtc_batch* batch, const kvtc_job* j
  *   kvtc_wide_encode  x_dev and layout as kvtc_encode_blocked (per-layer tensors [layers][tokens][1024]
  *                     are read in place: no concatenated copy); out_dev 16-byte aligned, out_cap >=
  *                     kvtc_wide_encoded_bytes(w, n_tokens) else KVTC_E_SMALL.  One launch per section.
- *   kvtc_wide_decode  x_out_dev and layout as kvtc_decode_blocked.  For bf16 output the caller passes
- *                     sum_dev, an fp32 workspace [n_tokens][p] (16-byte aligned) in which the sections are
- *                     summed before ONE rounding to bf16; for fp32 output they are summed in x_out_dev
- *                     itself and sum_dev is ignored (may be null).  Sections after the first add with
- *                     hardware float adds in memory; the launches are ordered on the stream, so every
- *                     element receives its terms in section order and results are reproducible.
+ *   kvtc_wide_decode  x_out_dev and layout as kvtc_decode_blocked.  For bf16 output of a plan of several sections
+ *                     the caller passes sum_dev, an fp32 workspace [n_tokens][p] (16-byte aligned): all sections
+ *                     but the last are summed there, and the last section's launch reads that sum, adds its own
+ *                     part and rounds to bf16 ONCE; for fp32 output the sections are summed in x_out_dev itself and
+ *                     sum_dev is ignored (may be null; also for a plan of one section).  Sections between the first
+ *                     and the last add with hardware float adds in memory; the launches are ordered on the stream,
+ *                     so every element receives its terms in section order and results are reproducible.
  * Neither call allocates or synchronises.
  */
 typedef struct kvtc_wide kvtc_wide;

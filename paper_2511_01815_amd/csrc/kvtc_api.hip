@@ -503,7 +503,8 @@ static kvtc_status check_layout(const char* who, const void* x, kvtc_dtype dtype
 static kvtc_status encode_single(const char* who, const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens,
                                  const kvtc_layout* layout, void* out_dev, size_t out_cap, kvtc_stream stream);
 static kvtc_status decode_single(const char* who, const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens,
-                                 void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream, bool accumulate = false);
+                                 void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream, int accumulate = 0,
+                                 const float* sum_dev = nullptr, int64_t sum_ld = 0);
 
 kvtc_status kvtc_encode(const kvtc_plan* plan, const void* x_dev, kvtc_dtype dtype, int64_t n_tokens, int64_t ld_x,
                         void* out_dev, size_t out_cap, kvtc_stream stream) {
@@ -569,8 +570,11 @@ static kvtc_status encode_single(const char* who, const kvtc_plan* plan, const v
 }
 
 static kvtc_status decode_single(const char* who, const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens,
-                                 void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream, bool accumulate) {
-    if (accumulate && dtype != KVTC_F32) return fail(KVTC_E_ARG, "%s: sections are summed in fp32 only", who);
+                                 void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream, int accumulate,
+                                 const float* sum_dev, int64_t sum_ld) {
+    // accumulate: 0 = store; 1 = add into the fp32 output; 2 = bf16 output = round(sum_dev + product)
+    if ((accumulate == 1 && dtype != KVTC_F32) || (accumulate == 2 && (dtype != KVTC_BF16 || !sum_dev || sum_ld < plan->h.p)))
+        return fail(KVTC_E_ARG, "%s: bad combination of section mode and output type", who);
     if (!plan) return fail(KVTC_E_ARG, "kvtc_decode: null plan");
     if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_decode: n_tokens=%lld", (long long)n_tokens);
     if (n_tokens == 0) return KVTC_OK;
@@ -593,7 +597,9 @@ static kvtc_status decode_single(const char* who, const kvtc_plan* plan, const v
     a.x_blk_jump = xl.blk_jump;
     a.stream_buf = const_cast<void*>(in_dev);
     a.cap = in_bytes;
-    a.dec_accumulate = accumulate ? 1 : 0;
+    a.dec_accumulate = accumulate;
+    a.dec_sum = sum_dev;
+    a.dec_sum_ld = sum_ld;
     const int slots = cu_count() * plan->h.dec_wgs;
     // A tensor short enough for all its 128-token tiles to run at once takes the variant with one token
     // tile per wave (same plan data: it depends on the padded width only).
@@ -997,25 +1003,6 @@ namespace {
 
 constexpr int kSectionCoords = 1024, kSectionGroups = 64;
 
-// fp32 rows [n_tokens][p] (contiguous) -> bf16 at the caller's layout, rounding to nearest even; 8 features per thread
-__global__ void __launch_bounds__(256) round_to_bf16_kernel(const float* src, uint16_t* dst, int64_t n_tokens, int p, int64_t token_stride,
-                                                           int blk_log2, int64_t blk_jump) {
-    const int per_row = p / 8;
-    const int64_t total = n_tokens * per_row;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t t = i / per_row;
-        const int f = (int)(i - t * per_row) * 8;
-        const float4 a = *reinterpret_cast<const float4*>(src + t * p + f);
-        const float4 b = *reinterpret_cast<const float4*>(src + t * p + f + 4);
-        typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-        bf16x8 v;
-        v[0] = (__bf16)a.x; v[1] = (__bf16)a.y; v[2] = (__bf16)a.z; v[3] = (__bf16)a.w;
-        v[4] = (__bf16)b.x; v[5] = (__bf16)b.y; v[6] = (__bf16)b.z; v[7] = (__bf16)b.w;
-        const int64_t off = t * token_stride + f + (blk_log2 ? (int64_t)(f >> blk_log2) * blk_jump : 0);
-        *reinterpret_cast<uint4*>(dst + off) = __builtin_bit_cast(uint4, v);
-    }
-}
-
 }  // namespace
 
 extern "C" {
@@ -1110,36 +1097,32 @@ kvtc_status kvtc_wide_decode(const kvtc_wide* w, const void* in_dev, size_t in_b
     if (!dtype_ok(dtype)) return fail(KVTC_E_ARG, "kvtc_wide_decode: unknown dtype %d", (int)dtype);
     if (in_bytes < kvtc_wide_encoded_bytes(w, n_tokens))
         return fail(KVTC_E_SMALL, "kvtc_wide_decode: in_bytes=%zu < %zu", in_bytes, kvtc_wide_encoded_bytes(w, n_tokens));
-    // the sections' products are summed in fp32: straight in the output when that is fp32, else in the caller's workspace
+    // the sections' products are summed in fp32: straight in the output when that is fp32; else in the caller's workspace,
+    // from which the last section's launch reads the sum of the others, adds its own part and rounds to bf16 once
     XLayout xl;
     kvtc_status st = check_layout("kvtc_wide_decode", x_out_dev, dtype, layout, w->p, n_tokens, &xl);
     if (st != KVTC_OK) return st;
     const kvtc_layout flat = {w->p, 0, 0, 0};
-    void* target = x_out_dev;
-    const kvtc_layout* tlay = layout;
-    if (dtype == KVTC_BF16) {
+    const size_t n_sec = w->sections.size();
+    if (dtype == KVTC_BF16 && n_sec > 1) {
         if (!sum_dev) return fail(KVTC_E_ARG, "kvtc_wide_decode: bf16 output needs the fp32 workspace sum_dev [n_tokens][p]");
         if (reinterpret_cast<uintptr_t>(sum_dev) & 15u) return fail(KVTC_E_ARG, "kvtc_wide_decode: sum_dev must be 16-byte aligned");
-        target = sum_dev;
-        tlay = &flat;
     }
     size_t pos = 0;
-    bool first = true;
-    for (const kvtc_plan* s : w->sections) {
+    for (size_t c = 0; c < n_sec; ++c) {
+        const kvtc_plan* s = w->sections[c];
         pos = align_up(pos, 16);
         const size_t bytes = s->record_bytes * (size_t)n_tokens;
-        st = decode_single("kvtc_wide_decode", s, static_cast<const char*>(in_dev) + pos, bytes, n_tokens, target, KVTC_F32, tlay, stream, !first);
+        const char* in = static_cast<const char*>(in_dev) + pos;
+        if (dtype == KVTC_F32)
+            st = decode_single("kvtc_wide_decode", s, in, bytes, n_tokens, x_out_dev, KVTC_F32, layout, stream, c == 0 ? 0 : 1);
+        else if (c + 1 == n_sec)
+            st = n_sec == 1 ? decode_single("kvtc_wide_decode", s, in, bytes, n_tokens, x_out_dev, KVTC_BF16, layout, stream)
+                            : decode_single("kvtc_wide_decode", s, in, bytes, n_tokens, x_out_dev, KVTC_BF16, layout, stream, 2, sum_dev, w->p);
+        else
+            st = decode_single("kvtc_wide_decode", s, in, bytes, n_tokens, sum_dev, KVTC_F32, &flat, stream, c == 0 ? 0 : 1);
         if (st != KVTC_OK) return st;
         pos += bytes;
-        first = false;
-    }
-    if (dtype == KVTC_BF16) {
-        const int64_t items = n_tokens * (w->p / 8);
-        const int grid = (int)std::min<int64_t>((items + 255) / 256, (int64_t)cu_count() * 8);
-        hipLaunchKernelGGL(round_to_bf16_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream), sum_dev,
-                           static_cast<uint16_t*>(x_out_dev), n_tokens, w->p, xl.ld, xl.blk_log2, xl.blk_jump);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return fail(KVTC_E_HIP, "kvtc_wide_decode: launch failed: %s", hipGetErrorString(e));
     }
     return KVTC_OK;
 }

@@ -117,7 +117,7 @@ __device__ __forceinline__ int issue_records(const KernelArgs& a, const TileRef&
 // published.  With `prefetch` the ring does not overlap them: the first basis slab is requested
 // before unpacking, and the records of the workgroup's next tile (if any) are requested during
 // the first step of the feature sweep.
-template <int NCT, int TT, typename OT, bool ACC>
+template <int NCT, int TT, typename OT, int ACC>
 __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr, const KernelArgs& a, uint4* work, uint4* ring,
                                             bool prefetch, bool has_next, const TileRef& next, const PlanDec& Pn) {
     constexpr int TOK_W = 32 * TT;
@@ -267,7 +267,7 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
             // accumulators need)
             uint32_t lrow = lane_row;
             asm volatile("" : "+v"(lrow));
-            if constexpr (ACC) {
+            if constexpr (ACC == 1) {
                 // a further section of a sectioned plan: its part of the product is ADDED to what the earlier
                 // sections left in the fp32 output (hardware float adds in memory, nothing returned).  Rows past
                 // the tensor's end are skipped, not redirected: adding the last row's values twice would be wrong.
@@ -282,6 +282,22 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
                         unsafeAtomicAdd(dst + 1, acc1[tt][i]);
                     }
                 }
+            } else if constexpr (ACC == 2) {
+                // the last section of a sectioned plan, bf16 output: the earlier sections' fp32 sum (rows of a.dec_sum_ld
+                // floats, features contiguous) plus this section's part, rounded to bf16 once and stored at the caller's layout
+                static_assert(sizeof(OT) == 2, "the final rounding is to bf16");
+                const char* sb = reinterpret_cast<const char*>(a.dec_sum) +
+                                 ((size_t)(tr.x_row0 + tok_tile0) * (size_t)a.dec_sum_ld + (size_t)(f0 / 2) * 64) * sizeof(float);
+                const uint32_t sld = (uint32_t)a.dec_sum_ld * (uint32_t)sizeof(float);
+#pragma unroll
+                for (int k = 0; k < NST; ++k) {
+                    const int tt = k / 16, i = k % 16;
+                    const uint32_t row = lrow + (uint32_t)(tt * 32 + 8 * (i / 4) + i % 4);
+                    if (row <= last_row) {
+                        const float2 part = *reinterpret_cast<const float2*>(sb + ((size_t)row * sld + 2u * lane_col));
+                        *reinterpret_cast<uint32_t*>(ob + (__umul24(row, ldb) + lane_col)) = pack_bf16x2(part.x + acc0[tt][i], part.y + acc1[tt][i]);
+                    }
+                }
             } else {
 #pragma unroll
                 for (int k = 0; k < NST; ++k) {
@@ -294,7 +310,7 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
             }
         }
         // (the adds are a data-dependent number of operations, so after them the wait is for everything)
-        if (more && !ACC) wait_vmem<NST>(); else wait_vmem<0>();
+        if (more && ACC == 0) wait_vmem<NST>(); else wait_vmem<0>();
         __syncthreads();
     }
 }
@@ -314,7 +330,7 @@ __device__ __forceinline__ void decode_tile(const PlanDec& P, const TileRef& tr,
 template <int TT, int CLS> constexpr int dec_wgs_per_cu() { return CLS <= 4 ? 3 : (CLS <= 10 ? 2 : 1); }
 
 // The widths built for each class; a plan's tile count is rounded up to the next of them at plan creation.
-template <int CLS, int TT, typename OT, bool ACC>
+template <int CLS, int TT, typename OT, int ACC>
 __device__ __forceinline__ void decode_tile_of_class(const PlanDec& P, const TileRef& tr, const KernelArgs& a, uint4* work, uint4* ring,
                                                      bool prefetch, bool has_next, const TileRef& next, const PlanDec& Pn) {
 #define KVTC_W(N) case N: decode_tile<N, TT, OT, ACC>(P, tr, a, work, ring, prefetch, has_next, next, Pn); break;
@@ -332,7 +348,7 @@ __device__ __forceinline__ void decode_tile_of_class(const PlanDec& P, const Til
 #undef KVTC_W
 }
 
-template <typename OT, int TT, int CLS, bool ACC = false>
+template <typename OT, int TT, int CLS, int ACC = 0>
 __global__ void __launch_bounds__(kThreads, (dec_wgs_per_cu<TT, CLS>())) kvtc_decode_kernel(const KernelArgs a) {
     extern __shared__ uint4 smem[];
     uint32_t* tile_start = reinterpret_cast<uint32_t*>(smem);
@@ -383,9 +399,12 @@ hipError_t launch_decode(const KernelArgs& a, kvtc_dtype dtype, int key, int gri
     switch (key) {
 #define KVTC_X(TT, CLS)                                                                                        \
     case (TT) * 100 + (CLS):                                                                                   \
-        fn = dtype == KVTC_BF16 ? reinterpret_cast<const void*>(&kvtc_decode_kernel<uint16_t, TT, CLS>)        \
-             : a.dec_accumulate ? reinterpret_cast<const void*>(&kvtc_decode_kernel<float, TT, CLS, true>)     \
-                                : reinterpret_cast<const void*>(&kvtc_decode_kernel<float, TT, CLS>);          \
+        if (dtype == KVTC_BF16)                                                                                \
+            fn = a.dec_accumulate == 2 ? reinterpret_cast<const void*>(&kvtc_decode_kernel<uint16_t, TT, CLS, 2>) \
+                                       : reinterpret_cast<const void*>(&kvtc_decode_kernel<uint16_t, TT, CLS>); \
+        else                                                                                                   \
+            fn = a.dec_accumulate == 1 ? reinterpret_cast<const void*>(&kvtc_decode_kernel<float, TT, CLS, 1>) \
+                                       : reinterpret_cast<const void*>(&kvtc_decode_kernel<float, TT, CLS>);   \
         break;
         KVTC_DEC_VARIANTS(KVTC_X)
 #undef KVTC_X

@@ -74,7 +74,10 @@ struct KernelArgs {
     int32_t enc_short;         // encode: this launch runs the short-job variants (jobs of at most enc_short_max tokens whose plan has one) ...
     int32_t enc_short_max;     // ... and the launches of the bulk variants leave those jobs alone; 0 = no job counts as short
     int32_t dec_short;         // decode: this launch runs the one-token-tile-per-wave variant of every plan (128-token tiles)
-    int32_t dec_accumulate;    // decode, fp32 output only: add the product to the output instead of storing it (further sections of a sectioned plan)
+    int32_t dec_accumulate;    // decode of a sectioned plan: 1 = fp32 output, add the product to the output instead of storing it (a further section);
+                               // 2 = bf16 output, store round(dec_sum + product) (the last section)
+    const float* dec_sum;      // mode 2: the earlier sections' fp32 sums, [tokens][dec_sum_ld], features contiguous
+    int64_t dec_sum_ld;
 };
 
 struct TileRef {

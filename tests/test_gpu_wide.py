@@ -145,8 +145,19 @@ def test_wide_arguments_are_checked_before_any_launch():
     buf = torch.zeros(1 << 14, dtype=torch.uint8, device=DEV)
     lay = kv.layout(p)
     assert L.kvtc_wide_encode(w.handle, buf.data_ptr(), 0, T, C.byref(lay), buf.data_ptr(), T * 32 - 1, None) == 3     # stream too small
-    assert L.kvtc_wide_decode(w.handle, buf.data_ptr(), T * 32, T, buf.data_ptr(), 0, C.byref(lay), None, None) == 1   # bf16 output without workspace
-    assert "workspace" in kv.kvtc_last_error()
     assert L.kvtc_wide_decode(w.handle, buf.data_ptr(), T * 32 - 1, T, buf.data_ptr(), 1, C.byref(lay), None, None) == 3
+    # a plan of two sections (65 groups) needs the fp32 workspace for bf16 output; a plan of one section does not
+    p2, r2 = 1088, 1040
+    V2 = ko.bf16_bits((rng.standard_normal((p2, r2)) / 32).astype(np.float32))
+    w2 = kv.WidePlan(p2, r2, np.zeros(p2, np.float32), V2, [(16, 2)] * 65)
+    assert w2.n_sections == 2
+    big = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
+    lay2 = kv.layout(p2)
+    nb2 = kv.kvtc_wide_encoded_bytes(w2.handle, T)
+    assert L.kvtc_wide_decode(w2.handle, big.data_ptr(), nb2, T, big.data_ptr() + 32768, 0, C.byref(lay2), None, None) == 1
+    assert "workspace" in kv.kvtc_last_error()
+    w2.close()
+    assert L.kvtc_wide_decode(w.handle, buf.data_ptr(), T * 32, T, buf.data_ptr() + 8192, 0, C.byref(lay), None, None) == 0
+    torch.cuda.synchronize()
     assert L.kvtc_wide_encode(w.handle, buf.data_ptr(), 0, 0, C.byref(lay), buf.data_ptr(), 0, None) == 0               # nothing to do
     w.close()
