@@ -572,10 +572,10 @@ static kvtc_status encode_single(const char* who, const kvtc_plan* plan, const v
 static kvtc_status decode_single(const char* who, const kvtc_plan* plan, const void* in_dev, size_t in_bytes, int64_t n_tokens,
                                  void* x_out_dev, kvtc_dtype dtype, const kvtc_layout* layout, kvtc_stream stream, int accumulate,
                                  const float* sum_dev, int64_t sum_ld) {
+    if (!plan) return fail(KVTC_E_ARG, "kvtc_decode: null plan");
     // accumulate: 0 = store; 1 = add into the fp32 output; 2 = bf16 output = round(sum_dev + product)
     if ((accumulate == 1 && dtype != KVTC_F32) || (accumulate == 2 && (dtype != KVTC_BF16 || !sum_dev || sum_ld < plan->h.p)))
         return fail(KVTC_E_ARG, "%s: bad combination of section mode and output type", who);
-    if (!plan) return fail(KVTC_E_ARG, "kvtc_decode: null plan");
     if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(KVTC_E_ARG, "kvtc_decode: n_tokens=%lld", (long long)n_tokens);
     if (n_tokens == 0) return KVTC_OK;
     if (!in_dev || !x_out_dev) return fail(KVTC_E_ARG, "kvtc_decode: null buffer");
