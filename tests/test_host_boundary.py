@@ -172,6 +172,50 @@ def test_rope_rejects_bad_arguments_before_any_launch():
     del ok
 
 
+def test_later_entry_points_reject_bad_arguments_before_any_launch():
+    """Sectioned plans, the lossless stage and the calibration passes: every argument error below is found on the host,
+    before any allocation or launch, so it needs no GPU."""
+    L = kv.lib()
+    h = C.c_void_p()
+    mu = np.zeros(256, np.float32)
+    V = np.zeros((256, 64), np.uint16)
+    grp = (kv.binding._Group * 2)(kv.binding._Group(32, 4, 0), kv.binding._Group(16, 4, 0))      # sums to 48, not 64
+    assert L.kvtc_wide_create(C.byref(h), 256, 64, mu.ctypes.data, V.ctypes.data, 2, C.cast(grp, C.c_void_p), None) == 1
+    assert "sum to" in kv.kvtc_last_error()
+    assert L.kvtc_wide_create(C.byref(h), 250, 64, mu.ctypes.data, V.ctypes.data, 2, C.cast(grp, C.c_void_p), None) == 1
+    assert L.kvtc_wide_create(C.byref(h), 256, 64, None, V.ctypes.data, 2, C.cast(grp, C.c_void_p), None) == 1
+    big = (kv.binding._Group * 1)(kv.binding._Group(2048, 4, 0))
+    assert L.kvtc_wide_create(C.byref(h), 4096, 2048, mu.ctypes.data, V.ctypes.data, 1, C.cast(big, C.c_void_p), None) == 1
+    assert L.kvtc_wide_sections(None) == 0 and L.kvtc_wide_record_bytes(None) == 0 and L.kvtc_wide_encoded_bytes(None, 5) == 0
+    lay = kv.layout(256)
+    assert L.kvtc_wide_encode(None, 16, 0, 4, C.byref(lay), 16, 64, None) == 1
+    assert L.kvtc_wide_decode(None, 16, 64, 4, 16, 0, C.byref(lay), None, None) == 1
+    # lossless stage
+    good = np.full((8, 256), 8, dtype=np.uint8)
+    assert L.kvtc_entropy_create(C.byref(h), 6, 1, good.ctypes.data, None) == 1
+    assert L.kvtc_entropy_create(C.byref(h), 580, 1, good.ctypes.data, None) == 2
+    assert L.kvtc_entropy_create(C.byref(h), 8, 0, good.ctypes.data, None) == 1
+    assert L.kvtc_entropy_create(C.byref(h), 8, 1, None, None) == 1
+    bad = good.copy()
+    bad[1, :2] = 1
+    assert L.kvtc_entropy_create(C.byref(h), 8, 1, bad.ctypes.data, None) == 1 and "prefix code" in kv.kvtc_last_error()
+    assert L.kvtc_entropy_bound(None, 100) == 0
+    assert L.kvtc_entropy_encode(None, 0, 16, 4, 16, 64, 16, None) == 1
+    assert L.kvtc_entropy_decode(None, 0, 16, 64, 4, 16, 64, None) == 1
+    assert L.kvtc_entropy_encode_batch(None, 16, 1, 4, 16, 64, 16, 64, 16, None) == 1
+    assert L.kvtc_entropy_decode_batch(None, 16, 1, 4, 16, 64, 16, 64, None) == 1
+    assert kv.ENTROPY_JOB_DTYPE.itemsize == 32
+    # calibration passes
+    assert L.kvtc_calib_block_errors(16, 4, 64, 16, 1, 9, 16, None) == 1
+    assert L.kvtc_calib_block_errors(None, 4, 64, 16, 1, 8, 16, None) == 1
+    assert L.kvtc_calib_block_errors(16, 4, 64, 16, 1, 8, 20, None) == 1          # output not 8-byte aligned
+    assert L.kvtc_calib_block_errors(16, 4, 64, 16, 0, 8, 16, None) == 0          # no blocks: nothing to do
+    assert L.kvtc_calib_moments(16, 0, 4, 100, C.byref(lay), 16, 16, None) == 1
+    assert L.kvtc_calib_moments(16, 0, 4, 256, None, 16, 16, None) == 1
+    assert L.kvtc_calib_moments(16, 0, 4, 256, C.byref(kv.layout(128)), 16, 16, None) == 1
+    assert L.kvtc_calib_moments(16, 0, 4, 256, C.byref(lay), 16, 20, None) == 1
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
