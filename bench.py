@@ -122,8 +122,28 @@ def append_step_latency(kv, batch, x, T, plan_of_job, R, stream_buf, dev, c=16, 
     torch.cuda.synchronize()
     assert int(status.item()) == 0, "an append did not fit its region"
     us = sorted(ev[2 * k].elapsed_time(ev[2 * k + 1]) * 1e3 for k in range(warmup, warmup + steps))
-    return {"median_us": us[len(us) // 2], "min_us": us[0], "caches": n_jobs, "new_tokens_per_cache": c,
-            "what": "kvtc_offsets_append + kvtc_encode_batch, GPU time between HIP events"}
+    # the same step recorded once as a HIP graph and replayed (the calls allocate nothing and synchronise nothing)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        kv.kvtc_offsets_append(batch.handle, jobs[0], n_jobs, region, coded[0], offs)
+        kv.kvtc_encode_batch(batch.handle, jobs[0], n_jobs, x, kv.KVTC_BF16, 1024, offs, stream_buf, cap, status)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        kv.kvtc_offsets_append(batch.handle, jobs[0], n_jobs, region, coded[0], offs)
+        kv.kvtc_encode_batch(batch.handle, jobs[0], n_jobs, x, kv.KVTC_BF16, 1024, offs, stream_buf, cap, status)
+    gev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * steps)]
+    for k in range(steps):
+        gev[2 * k].record()
+        graph.replay()
+        gev[2 * k + 1].record()
+    torch.cuda.synchronize()
+    gus = sorted(gev[2 * k].elapsed_time(gev[2 * k + 1]) * 1e3 for k in range(steps))
+    return {"median_us": us[len(us) // 2], "min_us": us[0], "graph_median_us": gus[len(gus) // 2], "graph_min_us": gus[0],
+            "caches": n_jobs, "new_tokens_per_cache": c,
+            "what": "kvtc_offsets_append + kvtc_encode_batch, GPU time between HIP events; graph_*: the same step recorded once as a HIP graph and replayed"}
 
 
 def ceilings(kv, src, dst, reps=7):
