@@ -241,8 +241,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c3", choices=["c3", "c2x32"],
-                    help="c3: 32 layers x {K,V}, a plan per tensor; c2x32: one layer's two plans x 32 seeded draws")
+    ap.add_argument("--workload", default="c3", choices=["c3", "c2x32", "c4layer", "c5layer"],
+                    help="c3: 32 layers x {K,V}, a plan per tensor; c2x32: one layer's two plans x 32 seeded draws; c4layer: one layer "
+                         "(K, V) of the long-context configuration, 131072 tokens at 20x; c5layer: one layer of the ragged batch, "
+                         "256 caches of 512..16384 tokens x {K,V} = 512 jobs at 40x")
     ap.add_argument("--cr", default="16", choices=["8", "16", "20", "40", "full"],
                     help="compression target of the calibrated plans (c3: 8, 16, 20); 'full' = hand-set full-rank plan (compute-bound, c2x32 only)")
     ap.add_argument("--layers", type=int, default=32, help="layers (c3) or independent draws of the layer (c2x32) per batch")
@@ -263,6 +265,10 @@ def main() -> int:
     if args.workload == "c3" and args.cr not in ("8", "16", "20"):
         print("bench.py: --workload c3 has plans at 8, 16 and 20; use --workload c2x32 for 40 and full", file=sys.stderr)
         return 2
+    if args.workload == "c4layer":
+        args.cr = "20"
+    if args.workload == "c5layer":
+        args.cr = "40"
 
     import numpy as np
     import torch
@@ -278,6 +284,7 @@ def main() -> int:
     torch.cuda.set_device(dev)
     p, T, NL = 1024, args.tokens, args.layers
     n_jobs = 2 * NL
+    lens = None                      # tokens per job; None = T for every job
 
     # ---- plans (data from the committed calibration bundles) and the synthetic layers they belong to ----
     if args.workload == "c3":
@@ -285,6 +292,18 @@ def main() -> int:
         plan_of_job = list(range(n_jobs))
         layers = [ks.make_layer(ks.layer_spec("c3", j // 2, j % 2)) for j in range(n_jobs)]
         draw_seed = [ks.TEST_DRAW] * n_jobs
+    elif args.workload in ("c4layer", "c5layer"):
+        wname, lidx = ("c4", 5) if args.workload == "c4layer" else ("c5", 9)
+        bundles = [kb.load_plan_arrays(f"{wname}_L{lidx:02d}_{kvn}_cr{args.cr}") for kvn in ("K", "V")]
+        two = [ks.make_layer(ks.layer_spec(wname, lidx, kvi)) for kvi in (0, 1)]
+        if args.workload == "c4layer":
+            lens = [ks.WORKLOADS["c4"].n_tokens] * 2
+        else:
+            lens = [int(v) for v in np.repeat(ks.ragged_lengths("c5"), 2)]
+        n_jobs = len(lens)
+        plan_of_job = [j % 2 for j in range(n_jobs)]
+        layers = [two[j % 2] for j in range(n_jobs)]
+        draw_seed = [500 + j for j in range(n_jobs)]
     else:
         tag = "full" if args.cr == "full" else f"cr{args.cr}"
         bundles = [kb.load_plan_arrays(f"c2_K_{tag}"), kb.load_plan_arrays(f"c2_V_{tag}")]
@@ -299,15 +318,19 @@ def main() -> int:
     r = [pl.r for pl in plans]
 
     # ---- inputs, resident in HBM ----
-    x = torch.empty((n_jobs * T, p), dtype=torch.bfloat16, device=dev)
+    if lens is None:
+        lens = [T] * n_jobs
+    row0 = [int(v) for v in np.concatenate([[0], np.cumsum(lens)[:-1]])]
+    n_tok = int(sum(lens))
+    x = torch.empty((n_tok, p), dtype=torch.bfloat16, device=dev)
     for j in range(n_jobs):
-        ks.draw_bf16_torch(layers[j], T, draw_seed[j], dev, out=x[j * T:(j + 1) * T])
+        ks.draw_bf16_torch(layers[j], lens[j], draw_seed[j], dev, out=x[row0[j]:row0[j] + lens[j]])
         if args.workload == "c3":
             layers[j]._mix32 = None          # 64 mixing matrices need not stay on the device
-    jobs = kv.make_jobs(plan_of_job, [T] * n_jobs, [j * T for j in range(n_jobs)])
+    jobs = kv.make_jobs(plan_of_job, lens, row0)
     jobs_dev = torch.from_numpy(jobs.view(np.uint8)).to(dev)
     offs = torch.zeros(n_jobs + 1, dtype=torch.int64, device=dev)
-    cap = sum(T * R[plan_of_job[j]] for j in range(n_jobs))
+    cap = sum(lens[j] * R[plan_of_job[j]] for j in range(n_jobs))
     stream_buf = torch.empty(cap, dtype=torch.uint8, device=dev)
     x_hat = torch.empty_like(x)
     status = torch.zeros(2, dtype=torch.int32, device=dev)
@@ -346,20 +369,20 @@ def main() -> int:
     enc_avg, dec_avg = statistics.fmean(enc_ms), statistics.fmean(dec_ms)
     enc_med, dec_med = statistics.median(enc_ms), statistics.median(dec_ms)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    raw_bytes = n_jobs * T * p * 2
+    raw_bytes = n_tok * p * 2
 
     # sanity of the timed work: reconstruction error of the last step is what the ratio should give
     with torch.no_grad():
         worst = 0.0
         for j in (0, 1, n_jobs - 1):
-            a = x[j * T:(j + 1) * T].float()
-            b = x_hat[j * T:(j + 1) * T].float()
+            a = x[row0[j]:row0[j] + lens[j]].float()
+            b = x_hat[row0[j]:row0[j] + lens[j]].float()
             worst = max(worst, float((b - a).norm() / (a - a.mean(0)).norm()))
-    assert worst < (0.3 if args.cr in ("8", "16", "full") else 0.5), worst
+    assert worst < (0.3 if args.cr in ("8", "16", "full") else (0.5 if args.cr == "20" else 0.7)), worst
 
     # ---- roofline of the dominant direction (per launch group: all jobs of the batch) ----
-    alg_bytes = sum(T * (2 * p + R[plan_of_job[j]]) for j in range(n_jobs))
-    flops = sum(T * 2 * p * r[plan_of_job[j]] for j in range(n_jobs))
+    alg_bytes = sum(lens[j] * (2 * p + R[plan_of_job[j]]) for j in range(n_jobs))
+    flops = sum(lens[j] * 2 * p * r[plan_of_job[j]] for j in range(n_jobs))
     dom, dom_ms = ("kvtc_encode_kernel", enc_avg) if enc_avg >= dec_avg else ("kvtc_decode_kernel", dec_avg)
     t_hbm = alg_bytes / (HBM_PEAK_GBPS * 1e9)
     t_mfma = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
@@ -370,7 +393,7 @@ def main() -> int:
     roof["frac"] = roof["achieved"] / roof["peak"]
     # HBM bytes per launch of that kernel from rocprofv3 TCC counters (FETCH_SIZE + WRITE_SIZE, each scaled by what the
     # same counter reads for a copy of known size): measured offline, read from the tracked summary under profiles/
-    full_size = NL == 32 and T == 32768
+    full_size = args.workload in ("c3", "c2x32") and NL == 32 and T == 32768
     roof["traffic"] = traffic_from_profiles(args.workload, args.cr, dom) if full_size else None
     roof["kernel"] = dom
     roof["algorithmic_bytes_per_launch"] = alg_bytes
@@ -387,6 +410,13 @@ def main() -> int:
     if args.workload == "c3":
         wl = (f"c3: {NL} layers x {{K,V}} x {T} tok x 1024 bf16 = {raw_bytes / 2**30:.2f} GiB raw KV, {len(plans)} per-tensor plans "
               f"at {args.cr}x (r {ranks[0]}..{ranks[-1]}, R {min(R)}..{max(R)} B) in one batch; step = offsets + encode + decode")
+    elif args.workload == "c4layer":
+        wl = (f"c4 layer: {{K,V}} x {lens[0]} tok x 1024 bf16 = {raw_bytes / 2**30:.2f} GiB raw KV at 20x (r={r[0]}/{r[1]}, R={R[0]}/{R[1]} B), "
+              f"two jobs in one batch; step = offsets + encode + decode")
+    elif args.workload == "c5layer":
+        wl = (f"c5 layer: 256 caches of {min(lens)}..{max(lens)} tokens (log-uniform, {n_tok // 2} in all) x {{K,V}} x 1024 bf16 = "
+              f"{raw_bytes / 2**30:.2f} GiB raw KV at 40x (r={r[0]}/{r[1]}, R={R[0]}/{R[1]} B), {n_jobs} jobs in one batch, stream offsets "
+              f"from the GPU prefix sum; step = offsets + encode + decode")
     else:
         wl = (f"c2 layer (K+V, {T} tok x 1024 bf16, {args.cr if args.cr == 'full' else args.cr + 'x'}, r={r[0]}/{r[1]}, R={R[0]}/{R[1]} B) "
               f"x {NL} seeded draws in one batch = {raw_bytes / 2**30:.2f} GiB raw KV; step = offsets + encode + decode")
@@ -405,7 +435,7 @@ def main() -> int:
     # run on the 16 tokens that left each cache's sliding window, all n_jobs caches in one batched launch,
     # each cache appending to a region of its own in the stream buffer.
     # (on request only: it launches the encode kernels many more times, which would blur a profile of this run)
-    if args.append:
+    if args.append and args.workload in ("c3", "c2x32"):
         result["append_step"] = append_step_latency(kv, batch, x, T, plan_of_job, R, stream_buf, dev)
     # What plain kernels reach on this machine, next to the published 8 TB/s and 2.5 PFLOP/s the fractions are quoted against.
     # The lossless stage over the coded stream (not part of `value`: the headline metric is the coder's two kernels).
@@ -417,8 +447,8 @@ def main() -> int:
     if not args.no_ceilings:
         result["ceilings"] = ceilings(kv, x, x_hat)
     if not args.no_cpu:
-        nt = min(args.cpu_tokens, T)
-        xs = [ks.bf16_bits_to_f32(x[j * T:j * T + nt].view(torch.int16).cpu().numpy().view(np.uint16)) for j in (0, 1)]
+        nt = min(args.cpu_tokens, lens[0], lens[1])
+        xs = [ks.bf16_bits_to_f32(x[row0[j]:row0[j] + nt].view(torch.int16).cpu().numpy().view(np.uint16)) for j in (0, 1)]
         result["cpu_baseline"] = cpu_baseline([bundles[plan_of_job[0]], bundles[plan_of_job[1]]], xs, p,
                                               tables[0] if tables is not None and "lossless" in result else None)
     else:

@@ -2,11 +2,13 @@
 "Method", mode "Calibration": PCA basis, mean and bit allocation are computed once per model
 and compression ratio and reused).
 
-Run from the repository root:  python oracle/make_plans.py [--only c2|c3] [--procs N]
+Run from the repository root:  python oracle/make_plans.py [--only c2|c3|c45] [--procs N]
 Calls only the oracle and the seeded input generator.  Output, under
 paper_2511_01815_amd/plans/:
   c2_<K|V>_cr<ratio>.npz, c2_<K|V>_full.npz   one plan per file (mean, kept basis columns as
                                               bf16 bit patterns, kept groups);
+  c4_L05_<K|V>_cr20.npz, c5_L09_<K|V>_cr40.npz one layer of the long-context and of the ragged-batch configuration at
+                                              their ratios (one plan per file, as the c2 files);
   c3_L<layer>_<K|V>.npz                       one tensor of the 32-layer cache per file: the mean,
                                               the leading PCA directions (bf16 bit patterns) up to
                                               the last coordinate any ratio keeps, and for each
@@ -57,6 +59,20 @@ def write_c2() -> None:
         print(path, "r", plan.r, "R", plan.record_bytes, flush=True)
 
 
+def write_layer(workload: str, layer_idx: int, cr: float) -> None:
+    """K and V plans of one layer of a multi-layer configuration at one ratio -> one-plan files."""
+    wl = ks.WORKLOADS[workload]
+    for kvi, name in enumerate(wl.kv):
+        spec = ks.layer_spec(workload, layer_idx, kvi)
+        layer = ks.make_layer(spec)
+        C = ks.bf16_bits_to_f32(ks.draw_bf16(layer, wl.n_calib, ks.CALIB_DRAW))
+        mu, V, S = ko.pca(C)
+        plan, info = ko.calibrate_from_pca(C, mu, V, S, cr, errors=ko.dp_errors(C, mu, V))
+        path = os.path.join(OUT_DIR, f"{workload}_L{layer_idx:02d}_{name}_cr{int(cr)}.npz")
+        ko.save_plan(path, plan, cr=cr, budget_bits=info["budget_bits"], seed=spec.seed, alpha=spec.alpha)
+        print(path, "r", plan.r, "R", plan.record_bytes, list(zip(plan.group_n.tolist(), plan.group_bits.tolist())), flush=True)
+
+
 def calibrate_c3_tensor(layer_kv):
     """The plans of one tensor of the 32-layer cache at every ratio of the sweep -> one file."""
     layer_idx, kvi = layer_kv
@@ -96,12 +112,15 @@ def write_c3(procs: int) -> None:
 
 def main() -> None:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--only", choices=["c2", "c3"], default=None)
+    ap.add_argument("--only", choices=["c2", "c3", "c45"], default=None)
     ap.add_argument("--procs", type=int, default=1, help="worker processes for the 64 tensors of c3")
     args = ap.parse_args()
     os.makedirs(OUT_DIR, exist_ok=True)
     if args.only in (None, "c2"):
         write_c2()
+    if args.only in (None, "c45"):
+        write_layer("c4", 5, 20.0)
+        write_layer("c5", 9, 40.0)
     if args.only in (None, "c3"):
         write_c3(args.procs)
 
