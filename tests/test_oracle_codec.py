@@ -454,3 +454,20 @@ def test_reciprocal_form_of_the_code_decision_against_the_divide_form():
             worst_rate = max(worst_rate, float((diff != 0).mean()))
     print(f"reciprocal vs divide form: at most {worst_rate:.2e} of entries differ, each by one code")
     assert worst_rate <= 2e-5
+
+
+def test_committed_single_layer_bundle_is_what_the_calibration_script_writes():
+    """The bundle of the ragged-batch configuration's layer 9 (K, 40x) that the benchmark loads equals the oracle's
+    calibration on that layer's seeded calibration draw."""
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    wl = ks.WORKLOADS["c5"]
+    L = ks.make_layer(ks.layer_spec("c5", 9, 0))
+    C = ks.bf16_bits_to_f32(ks.draw_bf16(L, wl.n_calib, ks.CALIB_DRAW))
+    mu, V, S = ko.pca(C)
+    plan, info = ko.calibrate_from_pca(C, mu, V, S, 40.0, errors=ko.dp_errors(C, mu, V))
+    z = np.load(os.path.join(root, "paper_2511_01815_amd", "plans", "c5_L09_K_cr40.npz"))
+    np.testing.assert_array_equal(z["v_bits"], plan.v_bits)
+    np.testing.assert_array_equal(z["mu32"], plan.mu32)
+    assert z["group_n"].tolist() == plan.group_n.tolist() and z["group_bits"].tolist() == plan.group_bits.tolist()
+    assert plan.record_bytes * 8 <= info["budget_bits"] == 384
